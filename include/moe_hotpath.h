@@ -1,0 +1,246 @@
+/*
+ * moe_hotpath.h -- C ABI of the MI355X (gfx950) MoE-layer hot path.
+ *
+ * One MoE block as the paper's Section 2.1 states it: the gate computes routing
+ * weights with a softmax and selects the top-k experts of every token, and the
+ * block output is the weighted sum of those experts' outputs,
+ *
+ *        e_j, w_j = Gate(a)          x' = sum_{j<k} w_j * Expert_{e_j}(a).
+ *
+ * An expert is the three linear maps gate_proj, up_proj, down_proj
+ * (Section 4.4) used as a SiLU-gated FFN.  Experts that are not resident in
+ * device memory are streamed from pinned host memory into fixed, pre-registered
+ * device slots on a side stream (Section 4.4: an on-demand double buffer plus a
+ * prefetch buffer in two groups, current layer / next layer) while the
+ * resident experts compute.  Where an expert's bytes come from never changes
+ * the result.
+ *
+ * Conventions
+ * -----------
+ *  - All pointers are DEVICE pointers unless the parameter name starts with
+ *    `host_` or the comment says "host".  The caller owns every buffer it
+ *    passes; the library owns only what moe_create() allocates.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Hot calls enqueue work on it and return; they never allocate device
+ *    memory.  Results are valid once the stream has been synchronised.
+ *  - Storage dtype MOE_BF16: X, Wr and expert matrices are bfloat16, products
+ *    are accumulated in float32 (router: float64), `out` is bfloat16.
+ *    MOE_F32: everything float32 (router accumulates in float64).
+ *  - Row-major layouts.  X [T,H]; Wr [E,H]; Wg, Wu [F,H]; Wd [H,F].
+ *  - A = T*k routed assignments, flat id i = t*k + j.  Shared experts (S of
+ *    them) see every token with weight one and are not part of the gate.
+ *  - Every entry point returns MOE_OK or a negative moe_status; nothing throws
+ *    or aborts across this boundary.  moe_last_error() gives the reason.
+ *  - Same inputs give bit-identical outputs from run to run, and outputs do
+ *    not depend on residency or prefetch masks.
+ *
+ * Limits: 1 <= k <= E <= 128; k <= 16; S <= 8; H and F multiples of 64
+ * (bf16: H a multiple of 64 and F of 64); T*k + S*T < 2^24.
+ */
+#ifndef MOE_HOTPATH_H
+#define MOE_HOTPATH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MOE_OK = 0,
+  MOE_ERR_INVALID_ARG = -1,   /* NULL pointer, shape outside the limits, ...  */
+  MOE_ERR_UNSUPPORTED = -2,   /* legal request this build cannot serve       */
+  MOE_ERR_WORKSPACE = -3,     /* workspace missing or too small              */
+  MOE_ERR_HIP = -4,           /* a HIP runtime call failed                   */
+  MOE_ERR_SLOT_EXHAUSTED = -5 /* no streaming slot can hold the request      */
+} moe_status;
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
+
+/* Problem shape of one call.  T may change from call to call. */
+typedef struct {
+  int32_t T;      /* tokens                               */
+  int32_t H;      /* hidden size                          */
+  int32_t E;      /* routed experts                       */
+  int32_t k;      /* experts per token                    */
+  int32_t F;      /* expert FFN width                     */
+  int32_t S;      /* shared (always-on) experts           */
+  int32_t dtype;  /* moe_dtype                            */
+} moe_shape;
+
+/* The three matrices of one expert (Section 4.4). */
+typedef struct {
+  const void* Wg; /* gate_proj [F,H] */
+  const void* Wu; /* up_proj   [F,H] */
+  const void* Wd; /* down_proj [H,F] */
+} moe_expert_ptrs;
+
+typedef struct moe_ctx moe_ctx;
+
+/* Library version string (static storage). */
+const char* moe_version(void);
+
+/* Reason of the calling thread's most recent failure (static/thread-local
+ * storage, valid until that thread's next failing call). */
+const char* moe_last_error(void);
+
+/* Bytes of device workspace that moe_layer_forward() (and therefore any single
+ * hot call) needs for `shape`.  Returns 0 if the shape is invalid.  The caller
+ * allocates it once (256-byte aligned) and passes it to the hot calls. */
+size_t moe_workspace_bytes(const moe_shape* shape);
+
+/* ---- a1 + a2: router GEMM, softmax, top-k, renormalised weights ----------
+ * Section 2.1 "Gate(a)".  logit[t,e] = bias[e] + sum_h X[t,h]*Wr[e,h],
+ * accumulated in float64 so that the selection matches a float64 reference
+ * bit for bit whenever neighbouring logits differ by more than ~1e-12.
+ * k rounds of arg-max over the logits, ties to the lowest expert index;
+ * topk_idx[t,:] is in order of selection (descending logit).
+ * topk_w[t,j] = softmax(logit[t,:])[e_j] / sum_j' softmax(logit[t,:])[e_j'].
+ *   X [T,H], Wr [E,H]  storage dtype;  bias [E] float32 or NULL (= zeros)
+ *   topk_idx [T,k] int32, topk_w [T,k] float32          (outputs)
+ *   logits_out [T,E] float64 or NULL                      (optional output)
+ * T == 0 is legal and does nothing. */
+moe_status moe_route(const moe_shape* shape, const void* X, const void* Wr,
+                     const float* bias, int32_t* topk_idx, float* topk_w,
+                     double* logits_out, void* stream);
+
+/* ---- a3: bucket the assignments by expert --------------------------------
+ * The per-expert pending-token counts of Section 4.3.2 (Premise 1) plus the
+ * permutation the grouped FFN consumes.  Stable: inside an expert's bucket the
+ * flat assignment ids ascend.
+ *   topk_idx [T,k] int32 (values in [0,E))
+ *   count [E], offset [E+1] (exclusive scan, offset[E] = A),
+ *   perm [A] (perm[p] = assignment at bucket position p),
+ *   inv_perm [A] (inv_perm[i] = bucket position of assignment i)  -- outputs
+ * An index outside [0,E) is not detected at enqueue time; such an assignment
+ * is dropped from every bucket and its inv_perm entry is set to -1. */
+moe_status moe_permute(const moe_shape* shape, const int32_t* topk_idx,
+                       int32_t* count, int32_t* offset, int32_t* perm,
+                       int32_t* inv_perm, void* stream);
+
+/* ---- a4: grouped SiLU-gated expert FFN over the active experts -----------
+ * Section 4.4's three matrices per expert.  For every expert e < E whose bit is
+ * set in the mask and whose bucket is not empty, and for every bucket position
+ * p in [offset[e], offset[e+1]) with token t = perm[p] / k:
+ *     h = silu(Wg_e . x_t) * (Wu_e . x_t),   Y[p,:] = Wd_e . h
+ * and for every shared expert s < S whose bit (E+s) is set, for every token t:
+ *     Y[A + s*T + t, :] = FFN_{E+s}(x_t).
+ * Experts with an empty bucket or a cleared bit read no weight bytes and leave
+ * their rows of Y untouched.
+ *   X [T,H] storage dtype; perm [A], offset [E+1] as produced by moe_permute
+ *   host_experts: HOST array [E+S] of device pointers (copied at enqueue time;
+ *                 entries of experts excluded by the mask may be NULL)
+ *   host_expert_mask: HOST array of ceil((E+S)/64) words, bit e of word e/64;
+ *                 NULL = all experts
+ *   Y [A + S*T, H] float32 (output)
+ *   workspace: device scratch of moe_workspace_bytes(shape) bytes (holds h;
+ *              bf16 storage rounds h to bfloat16 once, nearest even)
+ */
+moe_status moe_grouped_ffn(const moe_shape* shape, const void* X,
+                           const int32_t* perm, const int32_t* offset,
+                           const moe_expert_ptrs* host_experts,
+                           const uint64_t* host_expert_mask, float* Y,
+                           void* workspace, void* stream);
+
+/* ---- a5: weighted combine back to token order ----------------------------
+ * Section 2.1: x' = sum_j w_j * Expert_j(a).
+ *   out[t,:] = sum_{j<k} topk_w[t,j] * Y[inv_perm[t*k+j], :]
+ *            + sum_{s<S} Y[A + s*T + t, :]  (+ residual[t,:])
+ * summed in float32 in exactly that order, rounded once to the storage dtype.
+ *   residual [T,H] storage dtype or NULL;  out [T,H] storage dtype. */
+moe_status moe_combine(const moe_shape* shape, const float* Y,
+                       const float* topk_w, const int32_t* inv_perm,
+                       const void* residual, void* out, void* stream);
+
+/* ---- a6: context for expert streaming ------------------------------------
+ * Section 4.4: fixed device slots registered once, so that moving an expert is
+ * an overwrite of an existing buffer and nothing is allocated per transfer.
+ * moe_create allocates `n_ondemand_slots` (>= 2: one computing, one loading)
+ * plus 2 * `n_prefetch_slots_per_group` slots (group "current layer" and group
+ * "next layer", rotated after every layer), each big enough for one expert of
+ * `max_shape` (3*H*F elements), one side stream at default priority, events,
+ * and a small pinned host buffer for the per-expert counts.  Both slot counts
+ * may be 0 if every expert will always be resident.  Not a hot call. */
+moe_status moe_create(const moe_shape* max_shape, int32_t n_ondemand_slots,
+                      int32_t n_prefetch_slots_per_group, moe_ctx** out_ctx);
+
+/* Waits for the context's streams, frees slots, streams and events. */
+moe_status moe_destroy(moe_ctx* ctx);
+
+/* One layer's weights.  host arrays are indexed by expert, routed experts
+ * first, then shared experts. */
+typedef struct {
+  const void* Wr;                      /* [E,H] device                        */
+  const float* bias;                   /* [E] device or NULL                  */
+  const moe_expert_ptrs* host_dev;     /* HOST array [E+S]: device-resident
+                                          copies (entries of non-resident
+                                          experts are ignored)                */
+  const moe_expert_ptrs* host_pinned;  /* HOST array [E+S]: pinned host copies
+                                          (needed for non-resident experts;
+                                          may be NULL if all are resident)    */
+  uint64_t layer_id;                   /* names the layer in slot tags        */
+} moe_layer_desc;
+
+/* Filled on the host before moe_layer_forward returns. */
+typedef struct {
+  int32_t n_active;        /* routed experts with a non-empty bucket; -1 if the
+                              call did not need to read the counts back       */
+  int32_t n_resident;      /* active and resident                             */
+  int32_t n_hit;           /* active, non-resident, found in a prefetch slot  */
+  int32_t n_miss;          /* active, non-resident, loaded on demand          */
+  int32_t n_wasted;        /* prefetched for this layer but not active        */
+  int32_t n_prefetch_issued; /* copies started for the next layer             */
+  int64_t bytes_on_demand; /* host-to-device bytes queued on demand           */
+  int64_t bytes_prefetch;  /* host-to-device bytes queued as prefetch         */
+} moe_layer_stats;
+
+/* ---- the whole block ------------------------------------------------------
+ * route -> permute -> grouped FFN -> combine for one layer, with experts taken
+ * from wherever they live:
+ *   resident (bit set in host_resident_mask): computed first, from host_dev;
+ *   not resident, but prefetched for this layer_id into the current prefetch
+ *     group: a hit, computed from the slot once its copy has landed;
+ *   not resident, no slot: a miss, copied on demand through the on-demand
+ *     double buffer, queued AHEAD of any prefetch issued by this call;
+ *   empty bucket: skipped, nothing read, nothing copied.
+ * After the on-demand copies, copies of `host_prefetch_next_mask`'s experts of
+ * `next_layer` are queued into the next-layer prefetch group; after the layer
+ * the two groups swap roles.  Shared experts must be resident.
+ * If any routed expert is non-resident the call waits (on the host) for the
+ * router's counts before it can queue copies; with everything resident it
+ * never blocks.
+ *   out = block output (+ residual if given), [T,H] storage dtype.
+ *   host_resident_mask / host_prefetch_next_mask: HOST words, ceil(E/64) each;
+ *     NULL resident mask = all resident; NULL prefetch mask = none.
+ *   next_layer may be NULL.  stats may be NULL. */
+moe_status moe_layer_forward(moe_ctx* ctx, const moe_shape* shape,
+                             const moe_layer_desc* layer,
+                             const uint64_t* host_resident_mask,
+                             const moe_layer_desc* next_layer,
+                             const uint64_t* host_prefetch_next_mask,
+                             const void* X, const void* residual, void* out,
+                             void* workspace, void* stream,
+                             moe_layer_stats* stats);
+
+/* Host-side totals of the context's side stream since creation (or the last
+ * reset): bytes copied and the summed duration of the copies as measured by
+ * event pairs around each one.  Synchronises the side stream. */
+typedef struct {
+  int64_t bytes;
+  int64_t n_copies;
+  double copy_ms;
+} moe_stream_totals;
+moe_status moe_stream_totals_get(moe_ctx* ctx, moe_stream_totals* out, int32_t reset);
+
+/* Views into a workspace after moe_layer_forward (device pointers into
+ * `workspace`; for tests and harnesses).  Any output pointer may be NULL. */
+moe_status moe_workspace_views(const moe_shape* shape, void* workspace,
+                               int32_t** topk_idx, float** topk_w,
+                               int32_t** count, int32_t** offset,
+                               int32_t** perm, int32_t** inv_perm, float** Y);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_HOTPATH_H */

@@ -1,0 +1,90 @@
+// Internal helpers shared by the library's translation units (not part of the
+// public boundary).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "../../include/moe_hotpath.h"
+
+#define MOE_MAX_E 128
+#define MOE_MAX_K 16
+#define MOE_MAX_S 8
+#define MOE_MAX_GROUPS (MOE_MAX_E + MOE_MAX_S)
+#define MOE_WAVE 64
+
+namespace moe {
+
+moe_status fail(moe_status st, const char* fmt, ...);
+moe_status check_shape(const moe_shape* s, const char* who);
+
+#define MOE_HIP(expr)                                                          \
+  do {                                                                         \
+    hipError_t _e = (expr);                                                    \
+    if (_e != hipSuccess)                                                      \
+      return moe::fail(MOE_ERR_HIP, "%s: %s (%s:%d)", #expr,                  \
+                       hipGetErrorString(_e), __FILE__, __LINE__);             \
+  } while (0)
+
+#define MOE_REQUIRE(cond, ...)                                                 \
+  do {                                                                         \
+    if (!(cond)) return moe::fail(MOE_ERR_INVALID_ARG, __VA_ARGS__);           \
+  } while (0)
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Workspace carve-up (all offsets 256-byte aligned).
+struct WorkspaceLayout {
+  size_t topk_idx, topk_w, count, offset, perm, inv_perm, h, y, total;
+};
+WorkspaceLayout workspace_layout(const moe_shape& s);
+
+static inline int rows_total(const moe_shape& s) { return s.T * s.k + s.S * s.T; }
+static inline size_t elem_size(const moe_shape& s) { return s.dtype == MOE_F32 ? 4 : 2; }
+
+// Expert pointer table handed to kernels by value (kernel argument segment).
+struct ExpertTable {
+  const void* Wg[MOE_MAX_GROUPS];
+  const void* Wu[MOE_MAX_GROUPS];
+  const void* Wd[MOE_MAX_GROUPS];
+};
+
+// Per-launch list of experts to run (indices into ExpertTable), by value.
+struct GroupList {
+  int32_t n;
+  uint8_t id[MOE_MAX_GROUPS];
+};
+
+// internal launchers (each enqueues on `stream`, returns a status)
+moe_status launch_route(const moe_shape& s, const void* X, const void* Wr, const float* bias,
+                        int32_t* topk_idx, float* topk_w, double* logits_out, hipStream_t stream);
+moe_status launch_permute(const moe_shape& s, const int32_t* topk_idx, int32_t* count,
+                          int32_t* offset, int32_t* perm, int32_t* inv_perm, hipStream_t stream);
+moe_status launch_grouped_ffn(const moe_shape& s, const void* X, const int32_t* perm,
+                              const int32_t* offset, const ExpertTable& tab, const GroupList& groups,
+                              float* Y, void* h, hipStream_t stream);
+moe_status launch_ffn_gated(const moe_shape& s, const void* X, const int32_t* perm,
+                            const int32_t* offset, const ExpertTable& tab, const GroupList& groups,
+                            float* Y, void* h, hipStream_t stream, hipEvent_t wait_gu,
+                            hipEvent_t wait_d);
+moe_status launch_combine(const moe_shape& s, const float* Y, const float* topk_w,
+                          const int32_t* inv_perm, const void* residual, void* out,
+                          hipStream_t stream);
+
+// ---- device helpers -------------------------------------------------------
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) {
+  return __uint_as_float(((uint32_t)b) << 16);
+}
+
+// round to nearest even; inputs are finite in this library's use
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // quiet NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+}  // namespace moe

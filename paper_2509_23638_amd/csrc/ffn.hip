@@ -1,0 +1,367 @@
+// Grouped SiLU-gated expert FFN over the active experts (paper Section 4.4: an
+// expert is gate_proj, up_proj, down_proj; Section 2.1: only the top-k experts
+// of a token run).
+//
+// bf16 storage -- weight-streaming MFMA kernels
+// ---------------------------------------------
+// At decode sizes every active expert's weights are read once and used for a
+// handful of rows, so the kernels are built around the weight stream:
+//   * a wavefront owns 16 weight rows per matrix tile and walks the
+//     contraction dimension; lane (r = lane % 16, g = lane / 16) loads the 16
+//     bytes W[row0 + r][k0 + 8 g .. +7] straight into the register layout the
+//     A operand of v_mfma_f32_16x16x32_bf16 wants -- no LDS hop for weights;
+//   * the (few) activation rows are the B operand: a workgroup stages them
+//     through LDS one 128-wide k-chunk at a time, double buffered, already in
+//     fragment order, so every wave's B read is one linear ds_read_b128;
+//   * weights of chunk c+1 are in flight while chunk c multiplies.
+// Phase 1 (gate/up): tile 0 = 16 rows of Wg, tile 1 = the same rows of Wu, so
+// silu(g) * u happens in registers and h is written once, rounded to bf16.
+// Phase 2 (down): tile 0/1 = two neighbouring 16-row tiles of Wd; Y is float32.
+// Grid = (row slabs, experts in the launch list, 64-row token blocks); blocks
+// whose expert has an empty bucket (or no rows in that token block) exit at
+// once and read no weights.
+//
+// f32 storage -- plain float32 FMA kernels (one wavefront per output element
+// of a row block), for the small full-precision configuration.
+#include "common.h"
+
+namespace moe {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWaves = 4;           // wavefronts per workgroup
+constexpr int kThreads = kWaves * MOE_WAVE;
+constexpr int kKStep = 32;          // contraction depth of one MFMA
+constexpr int kStepsPerChunk = 4;   // k-steps staged per LDS buffer
+constexpr int kChunk = kKStep * kStepsPerChunk;  // 128
+constexpr int kMaxTiles = 4;        // 16-row activation tiles per pass
+constexpr int kTokBlock = 16 * kMaxTiles;        // 64 bucket rows per block
+constexpr int kFragBytes = MOE_WAVE * 16;        // one B fragment in LDS
+constexpr int kBufBytes = kMaxTiles * kStepsPerChunk * kFragBytes;  // 16 KiB
+
+enum { kGateUp = 0, kDown = 1 };
+
+struct FfnArgs {
+  const uint16_t* act;    // gate/up: X [T,H]; down: h [rows,F]
+  const int32_t* perm;
+  const int32_t* offset;
+  void* out;              // gate/up: h [rows,N] bf16; down: Y [rows,N] f32
+  int T, k, E, A;
+  int K;                  // contraction length
+  int N;                  // output width
+};
+
+__device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
+
+template <int MODE, int NT>
+struct Streamer {
+  const FfnArgs& a;
+  const uint16_t* w0;     // this lane's first element in tile 0
+  const uint16_t* w1;     // ... in tile 1
+  unsigned char* lds;
+  int lane, wave;
+  size_t act_off[NT];     // element offset of this lane's activation row per tile
+  bf16x8 wreg[2][kStepsPerChunk][2];
+  uint4 xreg[NT];
+  f32x4 acc0[NT], acc1[NT];
+
+  __device__ __forceinline__ Streamer(const FfnArgs& a_) : a(a_) {}
+
+  template <int SET>
+  __device__ __forceinline__ void load_weights(int c) {
+#pragma unroll
+    for (int s = 0; s < kStepsPerChunk; ++s) {
+      wreg[SET][s][0] = *reinterpret_cast<const bf16x8*>(w0 + (size_t)c * kChunk + s * kKStep);
+      wreg[SET][s][1] = *reinterpret_cast<const bf16x8*>(w1 + (size_t)c * kChunk + s * kKStep);
+    }
+  }
+
+  // wave w fetches k-step w of every tile of chunk c
+  __device__ __forceinline__ void load_act(int c) {
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+      xreg[t] = *reinterpret_cast<const uint4*>(a.act + act_off[t] + (size_t)c * kChunk +
+                                                wave * kKStep + (lane >> 4) * 8);
+  }
+
+  __device__ __forceinline__ void store_act(int buf) {
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+      *reinterpret_cast<uint4*>(lds + buf * kBufBytes +
+                                ((t * kStepsPerChunk + wave) * MOE_WAVE + lane) * 16) = xreg[t];
+  }
+
+  template <int SET>
+  __device__ __forceinline__ void multiply(int buf) {
+#pragma unroll
+    for (int s = 0; s < kStepsPerChunk; ++s) {
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        const bf16x8 b = *reinterpret_cast<const bf16x8*>(
+            lds + buf * kBufBytes + ((t * kStepsPerChunk + s) * MOE_WAVE + lane) * 16);
+        acc0[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[SET][s][0], b, acc0[t], 0, 0, 0);
+        acc1[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[SET][s][1], b, acc1[t], 0, 0, 0);
+      }
+    }
+  }
+
+  template <int SET>
+  __device__ __forceinline__ void step(int c, int nchunks) {
+    const bool more = c + 1 < nchunks;
+    if (more) {
+      load_act(c + 1);              // issued first: needed first (LDS hand-over)
+      load_weights<SET ^ 1>(c + 1);
+    }
+    multiply<SET>(c & 1);
+    if (more) store_act((c + 1) & 1);
+    __syncthreads();
+  }
+
+  __device__ __forceinline__ void run() {
+    const int nchunks = a.K / kChunk;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      acc0[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+      acc1[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    load_act(0);
+    load_weights<0>(0);
+    store_act(0);
+    __syncthreads();
+    int c = 0;
+    for (; c + 1 < nchunks; c += 2) {
+      step<0>(c, nchunks);
+      step<1>(c + 1, nchunks);
+    }
+    if (c < nchunks) step<0>(c, nchunks);
+  }
+};
+
+// One workgroup: expert `e`, output rows [n0, n0 + rows per WG), bucket rows
+// [r0, min(r0 + 64, row_end)).
+template <int MODE, int NT>
+__device__ __forceinline__ void ffn_block(const FfnArgs& a, const uint16_t* W0, const uint16_t* W1,
+                                          int n0, int r0, int row_end, int shared_base,
+                                          unsigned char* lds) {
+  Streamer<MODE, NT> st(a);
+  st.lds = lds;
+  st.lane = threadIdx.x & (MOE_WAVE - 1);
+  st.wave = threadIdx.x / MOE_WAVE;
+  const int r = st.lane & 15, g = st.lane >> 4;
+  int nrow0, nrow1;  // first output row of this wave's two tiles
+  if (MODE == kGateUp) {
+    nrow0 = nrow1 = n0 + st.wave * 16;
+  } else {
+    nrow0 = n0 + st.wave * 32;
+    nrow1 = nrow0 + 16;
+  }
+  st.w0 = W0 + (size_t)(nrow0 + r) * a.K + g * 8;
+  st.w1 = W1 + (size_t)(nrow1 + r) * a.K + g * 8;
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int p = min(r0 + t * 16 + r, row_end - 1);  // clamp; extra columns are dropped
+    int src;
+    if (MODE == kGateUp) src = shared_base >= 0 ? p - shared_base : a.perm[p] / a.k;
+    else src = p;
+    st.act_off[t] = (size_t)src * a.K;
+  }
+  st.run();
+
+  // D layout: lane holds rows 4*g .. 4*g+3 of the 16-row tile, column r
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int p = r0 + t * 16 + r;
+    if (p >= row_end) continue;
+    if (MODE == kGateUp) {
+      uint16_t hb[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) hb[j] = f32_to_bf16_bits(silu_f(st.acc0[t][j]) * st.acc1[t][j]);
+      uint2 pk;
+      pk.x = (uint32_t)hb[0] | ((uint32_t)hb[1] << 16);
+      pk.y = (uint32_t)hb[2] | ((uint32_t)hb[3] << 16);
+      uint16_t* h = static_cast<uint16_t*>(a.out);
+      *reinterpret_cast<uint2*>(h + (size_t)p * a.N + nrow0 + 4 * g) = pk;
+    } else {
+      float* y = static_cast<float*>(a.out);
+      *reinterpret_cast<float4*>(y + (size_t)p * a.N + nrow0 + 4 * g) =
+          make_float4(st.acc0[t][0], st.acc0[t][1], st.acc0[t][2], st.acc0[t][3]);
+      *reinterpret_cast<float4*>(y + (size_t)p * a.N + nrow1 + 4 * g) =
+          make_float4(st.acc1[t][0], st.acc1[t][1], st.acc1[t][2], st.acc1[t][3]);
+    }
+  }
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void ffn_stream_kernel(FfnArgs a, ExpertTable tab,
+                                                              GroupList groups) {
+  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * kBufBytes];
+  const int e = groups.id[blockIdx.y];
+  int row_begin, row_end, shared_base = -1;
+  if (e < a.E) {
+    row_begin = a.offset[e];
+    row_end = a.offset[e + 1];
+  } else {
+    row_begin = a.A + (e - a.E) * a.T;
+    row_end = row_begin + a.T;
+    shared_base = row_begin;
+  }
+  const int r0 = row_begin + blockIdx.z * kTokBlock;
+  if (r0 >= row_end) return;
+  const int nt = (min(row_end - r0, kTokBlock) + 15) / 16;
+  const uint16_t *W0, *W1;
+  int n0;
+  if (MODE == kGateUp) {
+    W0 = static_cast<const uint16_t*>(tab.Wg[e]);
+    W1 = static_cast<const uint16_t*>(tab.Wu[e]);
+    n0 = blockIdx.x * (kWaves * 16);
+  } else {
+    W0 = W1 = static_cast<const uint16_t*>(tab.Wd[e]);
+    n0 = blockIdx.x * (kWaves * 32);
+  }
+  switch (nt) {
+    case 1: ffn_block<MODE, 1>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
+    case 2: ffn_block<MODE, 2>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
+    case 3: ffn_block<MODE, 3>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
+    default: ffn_block<MODE, 4>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
+  }
+}
+
+// ---------------------------------------------------------------- float32 --
+// One wavefront per (bucket row, output column): lanes stride over the
+// contraction with float4 loads, float32 FMA, butterfly sum.
+__device__ __forceinline__ float wave_sum_f(float v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, MOE_WAVE);
+  return v;
+}
+
+struct F32Args {
+  const float* act;
+  const int32_t* perm;
+  const int32_t* offset;
+  float* out;
+  int T, k, E, A, K, N;
+};
+
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void ffn_f32_kernel(F32Args a, ExpertTable tab,
+                                                           GroupList groups) {
+  const int e = groups.id[blockIdx.y];
+  int row_begin, row_end, shared_base = -1;
+  if (e < a.E) {
+    row_begin = a.offset[e];
+    row_end = a.offset[e + 1];
+  } else {
+    row_begin = a.A + (e - a.E) * a.T;
+    row_end = row_begin + a.T;
+    shared_base = row_begin;
+  }
+  const int lane = threadIdx.x & (MOE_WAVE - 1);
+  const int wave = threadIdx.x / MOE_WAVE;
+  const int n = blockIdx.x * kWaves + wave;  // output column
+  if (n >= a.N) return;
+  const float* W0 = static_cast<const float*>(MODE == kGateUp ? tab.Wg[e] : tab.Wd[e]) + (size_t)n * a.K;
+  const float* W1 = MODE == kGateUp ? static_cast<const float*>(tab.Wu[e]) + (size_t)n * a.K : nullptr;
+  for (int p = row_begin + blockIdx.z; p < row_end; p += gridDim.z) {
+    int src;
+    if (MODE == kGateUp) src = shared_base >= 0 ? p - shared_base : a.perm[p] / a.k;
+    else src = p;
+    const float* x = a.act + (size_t)src * a.K;
+    float s0 = 0.f, s1 = 0.f;
+    for (int kk = lane * 4; kk < a.K; kk += MOE_WAVE * 4) {
+      const float4 xv = *reinterpret_cast<const float4*>(x + kk);
+      const float4 wv = *reinterpret_cast<const float4*>(W0 + kk);
+      s0 = fmaf(xv.x, wv.x, s0); s0 = fmaf(xv.y, wv.y, s0);
+      s0 = fmaf(xv.z, wv.z, s0); s0 = fmaf(xv.w, wv.w, s0);
+      if (MODE == kGateUp) {
+        const float4 uv = *reinterpret_cast<const float4*>(W1 + kk);
+        s1 = fmaf(xv.x, uv.x, s1); s1 = fmaf(xv.y, uv.y, s1);
+        s1 = fmaf(xv.z, uv.z, s1); s1 = fmaf(xv.w, uv.w, s1);
+      }
+    }
+    s0 = wave_sum_f(s0);
+    if (MODE == kGateUp) {
+      s1 = wave_sum_f(s1);
+      if (lane == 0) a.out[(size_t)p * a.N + n] = s0 / (1.0f + expf(-s0)) * s1;
+    } else {
+      if (lane == 0) a.out[(size_t)p * a.N + n] = s0;
+    }
+  }
+}
+
+}  // namespace
+
+// Both FFN phases for the experts in `groups`.  `wait_gu` / `wait_d` (may be
+// NULL) are events the stream waits on before the gate/up phase and before the
+// down phase: a streamed expert's first phase can start as soon as its gate
+// and up projections have landed.
+moe_status launch_ffn_gated(const moe_shape& s, const void* X, const int32_t* perm,
+                            const int32_t* offset, const ExpertTable& tab, const GroupList& groups,
+                            float* Y, void* h, hipStream_t stream, hipEvent_t wait_gu,
+                            hipEvent_t wait_d) {
+  if (groups.n == 0 || s.T == 0) return MOE_OK;
+  const int A = s.T * s.k;
+  if (wait_gu) MOE_HIP(hipStreamWaitEvent(stream, wait_gu, 0));
+  if (s.dtype == MOE_BF16) {
+    const int tok_blocks = (s.T + kTokBlock - 1) / kTokBlock;
+    FfnArgs gu{static_cast<const uint16_t*>(X), perm, offset, h, s.T, s.k, s.E, A, s.H, s.F};
+    hipLaunchKernelGGL((ffn_stream_kernel<kGateUp>), dim3(s.F / (kWaves * 16), groups.n, tok_blocks),
+                       dim3(kThreads), 0, stream, gu, tab, groups);
+    if (wait_d) MOE_HIP(hipStreamWaitEvent(stream, wait_d, 0));
+    FfnArgs dn{static_cast<const uint16_t*>(h), perm, offset, Y, s.T, s.k, s.E, A, s.F, s.H};
+    hipLaunchKernelGGL((ffn_stream_kernel<kDown>), dim3(s.H / (kWaves * 32), groups.n, tok_blocks),
+                       dim3(kThreads), 0, stream, dn, tab, groups);
+  } else {
+    const int zb = s.T < 64 ? s.T : 64;
+    F32Args gu{static_cast<const float*>(X), perm, offset, static_cast<float*>(h),
+               s.T, s.k, s.E, A, s.H, s.F};
+    hipLaunchKernelGGL((ffn_f32_kernel<kGateUp>), dim3((s.F + kWaves - 1) / kWaves, groups.n, zb),
+                       dim3(kThreads), 0, stream, gu, tab, groups);
+    if (wait_d) MOE_HIP(hipStreamWaitEvent(stream, wait_d, 0));
+    F32Args dn{static_cast<const float*>(h), perm, offset, Y, s.T, s.k, s.E, A, s.F, s.H};
+    hipLaunchKernelGGL((ffn_f32_kernel<kDown>), dim3((s.H + kWaves - 1) / kWaves, groups.n, zb),
+                       dim3(kThreads), 0, stream, dn, tab, groups);
+  }
+  MOE_HIP(hipGetLastError());
+  return MOE_OK;
+}
+
+moe_status launch_grouped_ffn(const moe_shape& s, const void* X, const int32_t* perm,
+                              const int32_t* offset, const ExpertTable& tab,
+                              const GroupList& groups, float* Y, void* h, hipStream_t stream) {
+  return launch_ffn_gated(s, X, perm, offset, tab, groups, Y, h, stream, nullptr, nullptr);
+}
+
+}  // namespace moe
+
+extern "C" moe_status moe_grouped_ffn(const moe_shape* shape, const void* X, const int32_t* perm,
+                                      const int32_t* offset, const moe_expert_ptrs* host_experts,
+                                      const uint64_t* host_expert_mask, float* Y, void* workspace,
+                                      void* stream) {
+  moe_status st = moe::check_shape(shape, "moe_grouped_ffn");
+  if (st != MOE_OK) return st;
+  if (shape->T == 0) return MOE_OK;
+  MOE_REQUIRE(X && perm && offset && host_experts && Y, "moe_grouped_ffn: NULL pointer argument");
+  if (!workspace) return moe::fail(MOE_ERR_WORKSPACE, "moe_grouped_ffn: NULL workspace");
+  moe::ExpertTable tab;
+  moe::GroupList groups;
+  groups.n = 0;
+  const int n = shape->E + shape->S;
+  for (int e = 0; e < n; ++e) {
+    const bool on = !host_expert_mask || ((host_expert_mask[e >> 6] >> (e & 63)) & 1ull);
+    tab.Wg[e] = host_experts[e].Wg;
+    tab.Wu[e] = host_experts[e].Wu;
+    tab.Wd[e] = host_experts[e].Wd;
+    if (on) {
+      MOE_REQUIRE(tab.Wg[e] && tab.Wu[e] && tab.Wd[e],
+                  "moe_grouped_ffn: expert %d is in the mask but has a NULL matrix", e);
+      groups.id[groups.n++] = (uint8_t)e;
+    }
+  }
+  const moe::WorkspaceLayout L = moe::workspace_layout(*shape);
+  return moe::launch_grouped_ffn(*shape, X, perm, offset, tab, groups, Y,
+                                 static_cast<char*>(workspace) + L.h,
+                                 static_cast<hipStream_t>(stream));
+}

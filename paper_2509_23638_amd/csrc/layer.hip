@@ -1,0 +1,401 @@
+// The whole MoE block (paper Section 2.1) with experts taken from wherever they
+// live, and the streaming of non-resident experts (Section 4.4).
+//
+// What is kept from Section 4.4: fixed device slots registered once (an
+// on-demand double buffer plus a prefetch buffer in two groups that rotate
+// every layer, so a prefetch for layer l+1 can never overwrite an expert layer
+// l still needs), pinned host memory with asynchronous copies, on-demand loads
+// queued ahead of prefetches, and sub-tensor granularity (gate and up
+// projections land first and the first FFN phase starts on them while the
+// down projection is still in flight).  Expert traffic is one ordered queue
+// (Section 2.3 observes concurrent expert transfers are no faster than serial
+// ones), here a single side stream at default priority.
+//
+// Slot hand-over is ordered with events only: `copied_*` (side stream, after
+// the bytes land) gates the compute stream; `released` (compute stream, after
+// the last kernel that reads the slot) gates the side stream's next overwrite.
+#include "common.h"
+
+#include <new>
+#include <vector>
+
+namespace moe {
+namespace {
+
+struct Slot {
+  char* mem = nullptr;
+  uint64_t layer_id = 0;
+  int expert = -1;
+  bool valid = false;        // holds (or is receiving) `expert` of `layer_id`
+  bool has_release = false;  // `released` has been recorded at least once
+  hipEvent_t copied_gu = nullptr, copied_d = nullptr, released = nullptr;
+};
+
+struct TimedCopy {
+  hipEvent_t start, stop;
+  int64_t bytes;
+};
+
+}  // namespace
+}  // namespace moe
+
+struct moe_ctx {
+  moe_shape max_shape;
+  size_t matrix_bytes = 0;  // one of the three matrices at max_shape
+  int device = 0;
+  std::vector<moe::Slot> ondemand;
+  std::vector<moe::Slot> prefetch[2];
+  int cur_group = 0;        // prefetch[cur_group] serves the layer being computed
+  int od_next = 0;
+  hipStream_t copy_stream = nullptr;
+  hipEvent_t ev_counts = nullptr;
+  int32_t* host_counts = nullptr;  // pinned, MOE_MAX_E ints
+  std::vector<moe::TimedCopy> pending;    // recorded, not yet harvested
+  std::vector<moe::TimedCopy> free_pairs; // reusable event pairs
+  int64_t tot_bytes = 0, tot_copies = 0;
+  double tot_ms = 0.0;
+};
+
+namespace moe {
+namespace {
+
+moe_status make_slot(Slot& s, size_t bytes) {
+  MOE_HIP(hipMalloc(reinterpret_cast<void**>(&s.mem), bytes));
+  MOE_HIP(hipEventCreateWithFlags(&s.copied_gu, hipEventDisableTiming));
+  MOE_HIP(hipEventCreateWithFlags(&s.copied_d, hipEventDisableTiming));
+  MOE_HIP(hipEventCreateWithFlags(&s.released, hipEventDisableTiming));
+  return MOE_OK;
+}
+
+void drop_slot(Slot& s) {
+  if (s.mem) (void)hipFree(s.mem);
+  if (s.copied_gu) (void)hipEventDestroy(s.copied_gu);
+  if (s.copied_d) (void)hipEventDestroy(s.copied_d);
+  if (s.released) (void)hipEventDestroy(s.released);
+  s = Slot();
+}
+
+moe_status harvest(moe_ctx* c, bool wait) {
+  size_t keep = 0;
+  for (size_t i = 0; i < c->pending.size(); ++i) {
+    TimedCopy& t = c->pending[i];
+    hipError_t q = wait ? hipEventSynchronize(t.stop) : hipEventQuery(t.stop);
+    if (q == hipSuccess) {
+      float ms = 0.f;
+      MOE_HIP(hipEventElapsedTime(&ms, t.start, t.stop));
+      c->tot_ms += ms;
+      c->tot_bytes += t.bytes;
+      c->tot_copies += 1;
+      c->free_pairs.push_back(t);
+    } else if (q == hipErrorNotReady) {
+      c->pending[keep++] = t;
+    } else {
+      return fail(MOE_ERR_HIP, "event query: %s", hipGetErrorString(q));
+    }
+  }
+  c->pending.resize(keep);
+  return MOE_OK;
+}
+
+moe_status timed_pair(moe_ctx* c, TimedCopy* out) {
+  if (c->free_pairs.empty() && c->pending.size() >= 64) {
+    moe_status st = harvest(c, false);
+    if (st != MOE_OK) return st;
+  }
+  if (!c->free_pairs.empty()) {
+    *out = c->free_pairs.back();
+    c->free_pairs.pop_back();
+    return MOE_OK;
+  }
+  MOE_HIP(hipEventCreate(&out->start));
+  MOE_HIP(hipEventCreate(&out->stop));
+  return MOE_OK;
+}
+
+// Queue the copy of one expert into `slot` on the side stream.
+moe_status queue_copy(moe_ctx* c, const moe_shape& s, Slot& slot, const moe_expert_ptrs& src,
+                      uint64_t layer_id, int expert) {
+  const size_t mb = (size_t)s.H * s.F * elem_size(s);
+  if (slot.has_release) MOE_HIP(hipStreamWaitEvent(c->copy_stream, slot.released, 0));
+  TimedCopy tc;
+  moe_status st = timed_pair(c, &tc);
+  if (st != MOE_OK) return st;
+  tc.bytes = (int64_t)(3 * mb);
+  MOE_HIP(hipEventRecord(tc.start, c->copy_stream));
+  // need order: the first FFN phase reads gate and up, the second reads down
+  MOE_HIP(hipMemcpyAsync(slot.mem, src.Wg, mb, hipMemcpyHostToDevice, c->copy_stream));
+  MOE_HIP(hipMemcpyAsync(slot.mem + mb, src.Wu, mb, hipMemcpyHostToDevice, c->copy_stream));
+  MOE_HIP(hipEventRecord(slot.copied_gu, c->copy_stream));
+  MOE_HIP(hipMemcpyAsync(slot.mem + 2 * mb, src.Wd, mb, hipMemcpyHostToDevice, c->copy_stream));
+  MOE_HIP(hipEventRecord(slot.copied_d, c->copy_stream));
+  MOE_HIP(hipEventRecord(tc.stop, c->copy_stream));
+  c->pending.push_back(tc);
+  slot.layer_id = layer_id;
+  slot.expert = expert;
+  slot.valid = true;
+  return MOE_OK;
+}
+
+inline bool bit(const uint64_t* m, int e) { return (m[e >> 6] >> (e & 63)) & 1ull; }
+
+}  // namespace
+
+}  // namespace moe
+
+extern "C" moe_status moe_create(const moe_shape* max_shape, int32_t n_ondemand_slots,
+                                 int32_t n_prefetch_slots_per_group, moe_ctx** out_ctx) {
+  moe_status st = moe::check_shape(max_shape, "moe_create");
+  if (st != MOE_OK) return st;
+  MOE_REQUIRE(out_ctx, "moe_create: NULL out_ctx");
+  MOE_REQUIRE(n_ondemand_slots >= 0 && n_prefetch_slots_per_group >= 0 &&
+                  n_ondemand_slots != 1 && n_ondemand_slots <= 64 &&
+                  n_prefetch_slots_per_group <= MOE_MAX_E,
+              "moe_create: on-demand slots must be 0 or >= 2 (double buffer), got %d / %d",
+              n_ondemand_slots, n_prefetch_slots_per_group);
+  moe_ctx* c = new (std::nothrow) moe_ctx();
+  if (!c) return moe::fail(MOE_ERR_HIP, "moe_create: out of host memory");
+  c->max_shape = *max_shape;
+  c->matrix_bytes = (size_t)max_shape->H * max_shape->F * moe::elem_size(*max_shape);
+  st = MOE_OK;
+  auto body = [&]() -> moe_status {
+    MOE_HIP(hipGetDevice(&c->device));
+    MOE_HIP(hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking));
+    MOE_HIP(hipEventCreateWithFlags(&c->ev_counts, hipEventDisableTiming));
+    MOE_HIP(hipHostMalloc(reinterpret_cast<void**>(&c->host_counts), MOE_MAX_E * sizeof(int32_t),
+                          hipHostMallocDefault));
+    c->ondemand.resize(n_ondemand_slots);
+    for (auto& s : c->ondemand) {
+      moe_status r = moe::make_slot(s, 3 * c->matrix_bytes);
+      if (r != MOE_OK) return r;
+    }
+    for (int g = 0; g < 2; ++g) {
+      c->prefetch[g].resize(n_prefetch_slots_per_group);
+      for (auto& s : c->prefetch[g]) {
+        moe_status r = moe::make_slot(s, 3 * c->matrix_bytes);
+        if (r != MOE_OK) return r;
+      }
+    }
+    return MOE_OK;
+  };
+  st = body();
+  if (st != MOE_OK) {
+    moe_destroy(c);
+    return st;
+  }
+  *out_ctx = c;
+  return MOE_OK;
+}
+
+extern "C" moe_status moe_destroy(moe_ctx* c) {
+  if (!c) return MOE_OK;
+  if (c->copy_stream) (void)hipStreamSynchronize(c->copy_stream);
+  (void)hipDeviceSynchronize();
+  for (auto& s : c->ondemand) moe::drop_slot(s);
+  for (int g = 0; g < 2; ++g)
+    for (auto& s : c->prefetch[g]) moe::drop_slot(s);
+  for (auto& t : c->pending) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
+  for (auto& t : c->free_pairs) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
+  if (c->ev_counts) (void)hipEventDestroy(c->ev_counts);
+  if (c->host_counts) (void)hipHostFree(c->host_counts);
+  if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
+  delete c;
+  return MOE_OK;
+}
+
+extern "C" moe_status moe_stream_totals_get(moe_ctx* c, moe_stream_totals* out, int32_t reset) {
+  MOE_REQUIRE(c && out, "moe_stream_totals_get: NULL argument");
+  MOE_HIP(hipStreamSynchronize(c->copy_stream));
+  moe_status st = moe::harvest(c, true);
+  if (st != MOE_OK) return st;
+  out->bytes = c->tot_bytes;
+  out->n_copies = c->tot_copies;
+  out->copy_ms = c->tot_ms;
+  if (reset) {
+    c->tot_bytes = 0;
+    c->tot_copies = 0;
+    c->tot_ms = 0.0;
+  }
+  return MOE_OK;
+}
+
+extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
+                                        const moe_layer_desc* layer,
+                                        const uint64_t* host_resident_mask,
+                                        const moe_layer_desc* next_layer,
+                                        const uint64_t* host_prefetch_next_mask, const void* X,
+                                        const void* residual, void* out, void* workspace,
+                                        void* stream_, moe_layer_stats* stats) {
+  using namespace moe;
+  moe_status st = check_shape(shape, "moe_layer_forward");
+  if (st != MOE_OK) return st;
+  const moe_shape& s = *shape;
+  MOE_REQUIRE(c && layer, "moe_layer_forward: NULL context or layer");
+  MOE_REQUIRE(layer->Wr && layer->host_dev, "moe_layer_forward: layer without router or expert table");
+  if (!workspace) return fail(MOE_ERR_WORKSPACE, "moe_layer_forward: NULL workspace");
+  if (stats) {
+    *stats = moe_layer_stats();
+    stats->n_active = -1;
+  }
+  if (s.T == 0) return MOE_OK;
+  MOE_REQUIRE(X && out, "moe_layer_forward: NULL X or out");
+  MOE_REQUIRE((size_t)s.H * s.F * elem_size(s) <= c->matrix_bytes || (c->ondemand.empty() && c->prefetch[0].empty()),
+              "moe_layer_forward: expert larger than the context's slots");
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  const WorkspaceLayout L = workspace_layout(s);
+  char* w = static_cast<char*>(workspace);
+  int32_t* topk_idx = reinterpret_cast<int32_t*>(w + L.topk_idx);
+  float* topk_w = reinterpret_cast<float*>(w + L.topk_w);
+  int32_t* count = reinterpret_cast<int32_t*>(w + L.count);
+  int32_t* offset = reinterpret_cast<int32_t*>(w + L.offset);
+  int32_t* perm = reinterpret_cast<int32_t*>(w + L.perm);
+  int32_t* inv_perm = reinterpret_cast<int32_t*>(w + L.inv_perm);
+  void* h = w + L.h;
+  float* Y = reinterpret_cast<float*>(w + L.y);
+  const size_t mb = (size_t)s.H * s.F * elem_size(s);
+
+  bool all_resident = true;
+  if (host_resident_mask)
+    for (int e = 0; e < s.E; ++e) all_resident = all_resident && bit(host_resident_mask, e);
+  for (int e = 0; e < s.E + s.S; ++e) {
+    const bool res = e >= s.E || !host_resident_mask || bit(host_resident_mask, e);
+    if (res)
+      MOE_REQUIRE(layer->host_dev[e].Wg && layer->host_dev[e].Wu && layer->host_dev[e].Wd,
+                  "moe_layer_forward: resident expert %d has a NULL device matrix", e);
+    else
+      MOE_REQUIRE(layer->host_pinned && layer->host_pinned[e].Wg && layer->host_pinned[e].Wu &&
+                      layer->host_pinned[e].Wd,
+                  "moe_layer_forward: non-resident expert %d has no pinned host copy", e);
+  }
+
+  st = launch_route(s, X, layer->Wr, layer->bias, topk_idx, topk_w, nullptr, stream);
+  if (st != MOE_OK) return st;
+  st = launch_permute(s, topk_idx, count, offset, perm, inv_perm, stream);
+  if (st != MOE_OK) return st;
+
+  ExpertTable tab;
+  for (int e = 0; e < s.E + s.S; ++e) {
+    tab.Wg[e] = layer->host_dev[e].Wg;
+    tab.Wu[e] = layer->host_dev[e].Wu;
+    tab.Wd[e] = layer->host_dev[e].Wd;
+  }
+  GroupList res_groups;
+  res_groups.n = 0;
+  std::vector<Slot>& cur = c->prefetch[c->cur_group];
+  std::vector<Slot>& nxt = c->prefetch[c->cur_group ^ 1];
+
+  if (all_resident) {
+    // nothing to decide on the host: kernels skip empty buckets by themselves
+    for (int e = 0; e < s.E + s.S; ++e) res_groups.id[res_groups.n++] = (uint8_t)e;
+    st = launch_ffn_gated(s, X, perm, offset, tab, res_groups, Y, h, stream, nullptr, nullptr);
+    if (st != MOE_OK) return st;
+  } else {
+    // the host must know which experts are active before it can queue copies
+    MOE_HIP(hipMemcpyAsync(c->host_counts, count, s.E * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+    MOE_HIP(hipEventRecord(c->ev_counts, stream));
+    MOE_HIP(hipEventSynchronize(c->ev_counts));
+    int n_active = 0, n_res = 0, n_hit = 0, n_miss = 0, n_wasted = 0;
+    int hit_slot[MOE_MAX_E];
+    std::vector<int> hits, misses;
+    for (int e = 0; e < s.E; ++e) {
+      hit_slot[e] = -1;
+      const bool active = c->host_counts[e] > 0;
+      const bool res = bit(host_resident_mask, e);
+      if (active) ++n_active;
+      if (active && res) {
+        ++n_res;
+        res_groups.id[res_groups.n++] = (uint8_t)e;
+      }
+    }
+    for (size_t i = 0; i < cur.size(); ++i) {
+      Slot& sl = cur[i];
+      if (!sl.valid || sl.layer_id != layer->layer_id || sl.expert < 0 || sl.expert >= s.E) continue;
+      const int e = sl.expert;
+      if (c->host_counts[e] > 0 && !bit(host_resident_mask, e) && hit_slot[e] < 0) {
+        hit_slot[e] = (int)i;
+        hits.push_back(e);
+        ++n_hit;
+      } else {
+        ++n_wasted;
+      }
+    }
+    for (int e = 0; e < s.E; ++e)
+      if (c->host_counts[e] > 0 && !bit(host_resident_mask, e) && hit_slot[e] < 0) misses.push_back(e);
+    n_miss = (int)misses.size();
+    if (n_miss > 0 && c->ondemand.empty())
+      return fail(MOE_ERR_SLOT_EXHAUSTED,
+                  "moe_layer_forward: %d expert(s) need an on-demand load but the context has no on-demand slots",
+                  n_miss);
+    for (int sx = 0; sx < s.S; ++sx) res_groups.id[res_groups.n++] = (uint8_t)(s.E + sx);
+
+    // resident experts first: they need nothing from the link
+    st = launch_ffn_gated(s, X, perm, offset, tab, res_groups, Y, h, stream, nullptr, nullptr);
+    if (st != MOE_OK) return st;
+    // prefetched experts: their copies were queued during the previous layer
+    for (int e : hits) {
+      Slot& sl = cur[hit_slot[e]];
+      tab.Wg[e] = sl.mem;
+      tab.Wu[e] = sl.mem + mb;
+      tab.Wd[e] = sl.mem + 2 * mb;
+      GroupList one;
+      one.n = 1;
+      one.id[0] = (uint8_t)e;
+      st = launch_ffn_gated(s, X, perm, offset, tab, one, Y, h, stream, sl.copied_gu, sl.copied_d);
+      if (st != MOE_OK) return st;
+      MOE_HIP(hipEventRecord(sl.released, stream));
+      sl.has_release = true;
+    }
+    // on-demand loads, through the double buffer, ahead of any new prefetch
+    for (int e : misses) {
+      Slot& sl = c->ondemand[c->od_next];
+      c->od_next = (c->od_next + 1) % (int)c->ondemand.size();
+      st = queue_copy(c, s, sl, layer->host_pinned[e], layer->layer_id, e);
+      if (st != MOE_OK) return st;
+      tab.Wg[e] = sl.mem;
+      tab.Wu[e] = sl.mem + mb;
+      tab.Wd[e] = sl.mem + 2 * mb;
+      GroupList one;
+      one.n = 1;
+      one.id[0] = (uint8_t)e;
+      st = launch_ffn_gated(s, X, perm, offset, tab, one, Y, h, stream, sl.copied_gu, sl.copied_d);
+      if (st != MOE_OK) return st;
+      MOE_HIP(hipEventRecord(sl.released, stream));
+      sl.has_release = true;
+      if (stats) stats->bytes_on_demand += (int64_t)(3 * mb);
+    }
+    if (stats) {
+      stats->n_active = n_active;
+      stats->n_resident = n_res;
+      stats->n_hit = n_hit;
+      stats->n_miss = n_miss;
+      stats->n_wasted = n_wasted;
+    }
+  }
+
+  // the current group has served this layer (its readers are queued and have
+  // recorded `released`); it becomes the target of the layer after next
+  for (Slot& sl : cur) sl.valid = false;
+
+  st = launch_combine(s, Y, topk_w, inv_perm, residual, out, stream);
+  if (st != MOE_OK) return st;
+
+  // prefetch for the next layer, behind every on-demand copy queued above
+  if (next_layer && host_prefetch_next_mask && !nxt.empty()) {
+    MOE_REQUIRE(next_layer->host_pinned, "moe_layer_forward: prefetch requested but next layer has no pinned copies");
+    size_t used = 0;
+    for (Slot& sl : nxt) sl.valid = false;
+    for (int e = 0; e < s.E && used < nxt.size(); ++e) {
+      if (!bit(host_prefetch_next_mask, e)) continue;
+      const moe_expert_ptrs& src = next_layer->host_pinned[e];
+      MOE_REQUIRE(src.Wg && src.Wu && src.Wd, "moe_layer_forward: prefetch of expert %d without a pinned copy", e);
+      st = queue_copy(c, s, nxt[used], src, next_layer->layer_id, e);
+      if (st != MOE_OK) return st;
+      ++used;
+      if (stats) {
+        stats->n_prefetch_issued += 1;
+        stats->bytes_prefetch += (int64_t)(3 * mb);
+      }
+    }
+  }
+  c->cur_group ^= 1;
+  return MOE_OK;
+}
