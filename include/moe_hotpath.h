@@ -34,8 +34,8 @@
  *  - Same inputs give bit-identical outputs from run to run, and outputs do
  *    not depend on residency or prefetch masks.
  *
- * Limits: 1 <= k <= E <= 128; k <= 16; S <= 8; H and F multiples of 64
- * (bf16: H a multiple of 64 and F of 64); T*k + S*T < 2^24.
+ * Limits: 1 <= k <= E <= 128; k <= 16; S <= 8; H and F multiples of 128
+ * (MOE_BF16) or of 8 (MOE_F32); T*(k+S) < 2^24.
  */
 #ifndef MOE_HOTPATH_H
 #define MOE_HOTPATH_H
@@ -232,6 +232,26 @@ typedef struct {
   double copy_ms;
 } moe_stream_totals;
 moe_status moe_stream_totals_get(moe_ctx* ctx, moe_stream_totals* out, int32_t reset);
+
+/* Optional per-phase timing of layers whose experts are all resident: when
+ * enabled, moe_layer_forward records an event on `stream` before the router
+ * and after each of the five kernels (route, permute, gate/up, down, combine);
+ * moe_phase_times_get waits for the recorded layers and returns the summed
+ * durations.  For measurement harnesses; off by default. */
+typedef struct {
+  double route_ms, permute_ms, gate_up_ms, down_ms, combine_ms;
+  int64_t n_layers;
+} moe_phase_times;
+moe_status moe_phase_timing(moe_ctx* ctx, int32_t enable);
+moe_status moe_phase_times_get(moe_ctx* ctx, moe_phase_times* out, int32_t reset);
+
+/* Measurement aids (not part of the method): a plain streaming copy
+ * dst[0:bytes] = src[0:bytes] and a plain streaming read of src[0:bytes]
+ * (sink4: 4 bytes of device scratch), 16 bytes per lane; `bytes` a multiple of
+ * 16.  They give the box's achievable HBM rate and a dispatch of known size
+ * for scaling hardware byte counters. */
+moe_status moe_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
+moe_status moe_probe_read(const void* src, size_t bytes, void* sink4, void* stream);
 
 /* Views into a workspace after moe_layer_forward (device pointers into
  * `workspace`; for tests and harnesses).  Any output pointer may be NULL. */

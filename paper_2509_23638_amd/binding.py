@@ -55,6 +55,11 @@ class moe_stream_totals(C.Structure):
     _fields_ = [("bytes", C.c_int64), ("n_copies", C.c_int64), ("copy_ms", C.c_double)]
 
 
+class moe_phase_times(C.Structure):
+    _fields_ = [("route_ms", C.c_double), ("permute_ms", C.c_double), ("gate_up_ms", C.c_double),
+                ("down_ms", C.c_double), ("combine_ms", C.c_double), ("n_layers", C.c_int64)]
+
+
 if not os.path.exists(LIB):
     raise ImportError(
         f"{LIB} is missing: build it first (python -m paper_2509_23638_amd.build, or "
@@ -78,14 +83,20 @@ _lib.moe_layer_forward.argtypes = [_P, _SH, C.POINTER(moe_layer_desc), C.POINTER
                                    C.POINTER(moe_layer_desc), C.POINTER(C.c_uint64),
                                    _P, _P, _P, _P, _P, C.POINTER(moe_layer_stats)]
 _lib.moe_stream_totals_get.argtypes = [_P, C.POINTER(moe_stream_totals), C.c_int32]
+_lib.moe_phase_timing.argtypes = [_P, C.c_int32]
+_lib.moe_phase_times_get.argtypes = [_P, C.POINTER(moe_phase_times), C.c_int32]
+_lib.moe_probe_copy.argtypes = [_P, _P, C.c_size_t, _P]
+_lib.moe_probe_read.argtypes = [_P, C.c_size_t, _P, _P]
 _lib.moe_workspace_views.argtypes = [_SH, _P] + [C.POINTER(_P)] * 7
 for _n in ("moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_create",
-           "moe_destroy", "moe_layer_forward", "moe_stream_totals_get", "moe_workspace_views"):
+           "moe_destroy", "moe_layer_forward", "moe_stream_totals_get", "moe_workspace_views",
+           "moe_phase_timing", "moe_phase_times_get", "moe_probe_copy", "moe_probe_read"):
     getattr(_lib, _n).restype = C.c_int32
 
 EXPORTS = ["moe_version", "moe_last_error", "moe_workspace_bytes", "moe_route", "moe_permute",
            "moe_grouped_ffn", "moe_combine", "moe_create", "moe_destroy", "moe_layer_forward",
-           "moe_stream_totals_get", "moe_workspace_views"]
+           "moe_stream_totals_get", "moe_workspace_views", "moe_phase_timing",
+           "moe_phase_times_get", "moe_probe_copy", "moe_probe_read"]
 
 
 def _check(st: int):
@@ -239,6 +250,14 @@ class Context:
         except Exception:
             pass
 
+    def phase_timing(self, enable: bool):
+        _check(_lib.moe_phase_timing(self._h, 1 if enable else 0))
+
+    def phase_times(self, reset=False) -> dict:
+        t = moe_phase_times()
+        _check(_lib.moe_phase_times_get(self._h, C.byref(t), 1 if reset else 0))
+        return {f: getattr(t, f) for f, _ in t._fields_}
+
     def stream_totals(self, reset=False) -> dict:
         t = moe_stream_totals()
         _check(_lib.moe_stream_totals_get(self._h, C.byref(t), 1 if reset else 0))
@@ -290,6 +309,18 @@ def moe_layer_forward(ctx: Context, shape, layer: Layer, X, out, workspace, resi
         _ptr(workspace, "workspace", (torch.uint8,), moe_workspace_bytes(shape)),
         _stream(stream), C.byref(stats) if stats is not None else None))
     return stats.as_dict() if stats is not None else None
+
+
+def moe_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None):
+    n = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() < n:
+        raise ValueError("dst smaller than src")
+    _check(_lib.moe_probe_copy(_ptr(dst, "dst"), _ptr(src, "src"), n, _stream(stream)))
+
+
+def moe_probe_read(src: torch.Tensor, sink: torch.Tensor, stream=None):
+    n = src.numel() * src.element_size()
+    _check(_lib.moe_probe_read(_ptr(src, "src"), n, _ptr(sink, "sink", None, 1), _stream(stream)))
 
 
 def moe_workspace_views(shape, workspace: torch.Tensor) -> dict:

@@ -66,10 +66,16 @@ moe_status launch_permute(const moe_shape& s, const int32_t* topk_idx, int32_t* 
 moe_status launch_grouped_ffn(const moe_shape& s, const void* X, const int32_t* perm,
                               const int32_t* offset, const ExpertTable& tab, const GroupList& groups,
                               float* Y, void* h, hipStream_t stream);
+moe_status launch_ffn_gate_up(const moe_shape& s, const void* X, const int32_t* perm,
+                              const int32_t* offset, const ExpertTable& tab,
+                              const GroupList& groups, void* h, hipStream_t stream);
+moe_status launch_ffn_down(const moe_shape& s, const void* h, const int32_t* perm,
+                           const int32_t* offset, const ExpertTable& tab, const GroupList& groups,
+                           float* Y, hipStream_t stream);
 moe_status launch_ffn_gated(const moe_shape& s, const void* X, const int32_t* perm,
                             const int32_t* offset, const ExpertTable& tab, const GroupList& groups,
                             float* Y, void* h, hipStream_t stream, hipEvent_t wait_gu,
-                            hipEvent_t wait_d);
+                            hipEvent_t wait_d, hipEvent_t mid);
 moe_status launch_combine(const moe_shape& s, const float* Y, const float* topk_w,
                           const int32_t* inv_perm, const void* residual, void* out,
                           hipStream_t stream);

@@ -293,33 +293,41 @@ __global__ __launch_bounds__(kThreads) void ffn_f32_kernel(F32Args a, ExpertTabl
 
 }  // namespace
 
-// Both FFN phases for the experts in `groups`.  `wait_gu` / `wait_d` (may be
-// NULL) are events the stream waits on before the gate/up phase and before the
-// down phase: a streamed expert's first phase can start as soon as its gate
-// and up projections have landed.
-moe_status launch_ffn_gated(const moe_shape& s, const void* X, const int32_t* perm,
-                            const int32_t* offset, const ExpertTable& tab, const GroupList& groups,
-                            float* Y, void* h, hipStream_t stream, hipEvent_t wait_gu,
-                            hipEvent_t wait_d) {
+// Phase 1 (gate and up projections, SiLU gate) for the experts in `groups`.
+moe_status launch_ffn_gate_up(const moe_shape& s, const void* X, const int32_t* perm,
+                              const int32_t* offset, const ExpertTable& tab,
+                              const GroupList& groups, void* h, hipStream_t stream) {
   if (groups.n == 0 || s.T == 0) return MOE_OK;
   const int A = s.T * s.k;
-  if (wait_gu) MOE_HIP(hipStreamWaitEvent(stream, wait_gu, 0));
   if (s.dtype == MOE_BF16) {
     const int tok_blocks = (s.T + kTokBlock - 1) / kTokBlock;
     FfnArgs gu{static_cast<const uint16_t*>(X), perm, offset, h, s.T, s.k, s.E, A, s.H, s.F};
     hipLaunchKernelGGL((ffn_stream_kernel<kGateUp>), dim3(s.F / (kWaves * 16), groups.n, tok_blocks),
                        dim3(kThreads), 0, stream, gu, tab, groups);
-    if (wait_d) MOE_HIP(hipStreamWaitEvent(stream, wait_d, 0));
-    FfnArgs dn{static_cast<const uint16_t*>(h), perm, offset, Y, s.T, s.k, s.E, A, s.F, s.H};
-    hipLaunchKernelGGL((ffn_stream_kernel<kDown>), dim3(s.H / (kWaves * 32), groups.n, tok_blocks),
-                       dim3(kThreads), 0, stream, dn, tab, groups);
   } else {
     const int zb = s.T < 64 ? s.T : 64;
     F32Args gu{static_cast<const float*>(X), perm, offset, static_cast<float*>(h),
                s.T, s.k, s.E, A, s.H, s.F};
     hipLaunchKernelGGL((ffn_f32_kernel<kGateUp>), dim3((s.F + kWaves - 1) / kWaves, groups.n, zb),
                        dim3(kThreads), 0, stream, gu, tab, groups);
-    if (wait_d) MOE_HIP(hipStreamWaitEvent(stream, wait_d, 0));
+  }
+  MOE_HIP(hipGetLastError());
+  return MOE_OK;
+}
+
+// Phase 2 (down projection) for the experts in `groups`.
+moe_status launch_ffn_down(const moe_shape& s, const void* h, const int32_t* perm,
+                           const int32_t* offset, const ExpertTable& tab, const GroupList& groups,
+                           float* Y, hipStream_t stream) {
+  if (groups.n == 0 || s.T == 0) return MOE_OK;
+  const int A = s.T * s.k;
+  if (s.dtype == MOE_BF16) {
+    const int tok_blocks = (s.T + kTokBlock - 1) / kTokBlock;
+    FfnArgs dn{static_cast<const uint16_t*>(h), perm, offset, Y, s.T, s.k, s.E, A, s.F, s.H};
+    hipLaunchKernelGGL((ffn_stream_kernel<kDown>), dim3(s.H / (kWaves * 32), groups.n, tok_blocks),
+                       dim3(kThreads), 0, stream, dn, tab, groups);
+  } else {
+    const int zb = s.T < 64 ? s.T : 64;
     F32Args dn{static_cast<const float*>(h), perm, offset, Y, s.T, s.k, s.E, A, s.F, s.H};
     hipLaunchKernelGGL((ffn_f32_kernel<kDown>), dim3((s.H + kWaves - 1) / kWaves, groups.n, zb),
                        dim3(kThreads), 0, stream, dn, tab, groups);
@@ -328,10 +336,26 @@ moe_status launch_ffn_gated(const moe_shape& s, const void* X, const int32_t* pe
   return MOE_OK;
 }
 
+// Both phases.  `wait_gu` / `wait_d` (may be NULL) are events the stream waits
+// on before the first and before the second phase: a streamed expert's first
+// phase can start as soon as its gate and up projections have landed.  `mid`
+// (may be NULL) is recorded between the phases.
+moe_status launch_ffn_gated(const moe_shape& s, const void* X, const int32_t* perm,
+                            const int32_t* offset, const ExpertTable& tab, const GroupList& groups,
+                            float* Y, void* h, hipStream_t stream, hipEvent_t wait_gu,
+                            hipEvent_t wait_d, hipEvent_t mid) {
+  if (wait_gu) MOE_HIP(hipStreamWaitEvent(stream, wait_gu, 0));
+  moe_status st = launch_ffn_gate_up(s, X, perm, offset, tab, groups, h, stream);
+  if (st != MOE_OK) return st;
+  if (mid) MOE_HIP(hipEventRecord(mid, stream));
+  if (wait_d) MOE_HIP(hipStreamWaitEvent(stream, wait_d, 0));
+  return launch_ffn_down(s, h, perm, offset, tab, groups, Y, stream);
+}
+
 moe_status launch_grouped_ffn(const moe_shape& s, const void* X, const int32_t* perm,
                               const int32_t* offset, const ExpertTable& tab,
                               const GroupList& groups, float* Y, void* h, hipStream_t stream) {
-  return launch_ffn_gated(s, X, perm, offset, tab, groups, Y, h, stream, nullptr, nullptr);
+  return launch_ffn_gated(s, X, perm, offset, tab, groups, Y, h, stream, nullptr, nullptr, nullptr);
 }
 
 }  // namespace moe

@@ -54,6 +54,12 @@ struct moe_ctx {
   std::vector<moe::TimedCopy> free_pairs; // reusable event pairs
   int64_t tot_bytes = 0, tot_copies = 0;
   double tot_ms = 0.0;
+  // optional per-phase timing of all-resident layers (6 boundary events each)
+  bool phase_timing = false;
+  std::vector<hipEvent_t> phase_events;  // 6 per timed layer, in call order
+  std::vector<hipEvent_t> phase_free;
+  double phase_ms[5] = {0, 0, 0, 0, 0};
+  int64_t phase_layers = 0;
 };
 
 namespace moe {
@@ -136,6 +142,19 @@ moe_status queue_copy(moe_ctx* c, const moe_shape& s, Slot& slot, const moe_expe
   return MOE_OK;
 }
 
+moe_status phase_event(moe_ctx* c, hipStream_t stream) {
+  hipEvent_t ev;
+  if (!c->phase_free.empty()) {
+    ev = c->phase_free.back();
+    c->phase_free.pop_back();
+  } else {
+    MOE_HIP(hipEventCreate(&ev));
+  }
+  MOE_HIP(hipEventRecord(ev, stream));
+  c->phase_events.push_back(ev);
+  return MOE_OK;
+}
+
 inline bool bit(const uint64_t* m, int e) { return (m[e >> 6] >> (e & 63)) & 1ull; }
 
 }  // namespace
@@ -195,6 +214,8 @@ extern "C" moe_status moe_destroy(moe_ctx* c) {
     for (auto& s : c->prefetch[g]) moe::drop_slot(s);
   for (auto& t : c->pending) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
   for (auto& t : c->free_pairs) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
+  for (auto& e : c->phase_events) (void)hipEventDestroy(e);
+  for (auto& e : c->phase_free) (void)hipEventDestroy(e);
   if (c->ev_counts) (void)hipEventDestroy(c->ev_counts);
   if (c->host_counts) (void)hipHostFree(c->host_counts);
   if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
@@ -267,10 +288,21 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
                   "moe_layer_forward: non-resident expert %d has no pinned host copy", e);
   }
 
+  const bool timed = c->phase_timing && all_resident;
+#define PHASE_MARK()                                   \
+  do {                                                 \
+    if (timed) {                                       \
+      moe_status _p = phase_event(c, stream);          \
+      if (_p != MOE_OK) return _p;                     \
+    }                                                  \
+  } while (0)
+  PHASE_MARK();
   st = launch_route(s, X, layer->Wr, layer->bias, topk_idx, topk_w, nullptr, stream);
   if (st != MOE_OK) return st;
+  PHASE_MARK();
   st = launch_permute(s, topk_idx, count, offset, perm, inv_perm, stream);
   if (st != MOE_OK) return st;
+  PHASE_MARK();
 
   ExpertTable tab;
   for (int e = 0; e < s.E + s.S; ++e) {
@@ -286,8 +318,12 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
   if (all_resident) {
     // nothing to decide on the host: kernels skip empty buckets by themselves
     for (int e = 0; e < s.E + s.S; ++e) res_groups.id[res_groups.n++] = (uint8_t)e;
-    st = launch_ffn_gated(s, X, perm, offset, tab, res_groups, Y, h, stream, nullptr, nullptr);
+    st = launch_ffn_gate_up(s, X, perm, offset, tab, res_groups, h, stream);
     if (st != MOE_OK) return st;
+    PHASE_MARK();
+    st = launch_ffn_down(s, h, perm, offset, tab, res_groups, Y, stream);
+    if (st != MOE_OK) return st;
+    PHASE_MARK();
   } else {
     // the host must know which experts are active before it can queue copies
     MOE_HIP(hipMemcpyAsync(c->host_counts, count, s.E * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
@@ -328,7 +364,7 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
     for (int sx = 0; sx < s.S; ++sx) res_groups.id[res_groups.n++] = (uint8_t)(s.E + sx);
 
     // resident experts first: they need nothing from the link
-    st = launch_ffn_gated(s, X, perm, offset, tab, res_groups, Y, h, stream, nullptr, nullptr);
+    st = launch_ffn_gated(s, X, perm, offset, tab, res_groups, Y, h, stream, nullptr, nullptr, nullptr);
     if (st != MOE_OK) return st;
     // prefetched experts: their copies were queued during the previous layer
     for (int e : hits) {
@@ -339,7 +375,7 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
       GroupList one;
       one.n = 1;
       one.id[0] = (uint8_t)e;
-      st = launch_ffn_gated(s, X, perm, offset, tab, one, Y, h, stream, sl.copied_gu, sl.copied_d);
+      st = launch_ffn_gated(s, X, perm, offset, tab, one, Y, h, stream, sl.copied_gu, sl.copied_d, nullptr);
       if (st != MOE_OK) return st;
       MOE_HIP(hipEventRecord(sl.released, stream));
       sl.has_release = true;
@@ -356,7 +392,7 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
       GroupList one;
       one.n = 1;
       one.id[0] = (uint8_t)e;
-      st = launch_ffn_gated(s, X, perm, offset, tab, one, Y, h, stream, sl.copied_gu, sl.copied_d);
+      st = launch_ffn_gated(s, X, perm, offset, tab, one, Y, h, stream, sl.copied_gu, sl.copied_d, nullptr);
       if (st != MOE_OK) return st;
       MOE_HIP(hipEventRecord(sl.released, stream));
       sl.has_release = true;
@@ -377,6 +413,8 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
 
   st = launch_combine(s, Y, topk_w, inv_perm, residual, out, stream);
   if (st != MOE_OK) return st;
+  PHASE_MARK();
+#undef PHASE_MARK
 
   // prefetch for the next layer, behind every on-demand copy queued above
   if (next_layer && host_prefetch_next_mask && !nxt.empty()) {
@@ -397,5 +435,37 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
     }
   }
   c->cur_group ^= 1;
+  return MOE_OK;
+}
+
+extern "C" moe_status moe_phase_timing(moe_ctx* c, int32_t enable) {
+  MOE_REQUIRE(c, "moe_phase_timing: NULL context");
+  c->phase_timing = enable != 0;
+  return MOE_OK;
+}
+
+extern "C" moe_status moe_phase_times_get(moe_ctx* c, moe_phase_times* out, int32_t reset) {
+  MOE_REQUIRE(c && out, "moe_phase_times_get: NULL argument");
+  for (size_t i = 0; i + 6 <= c->phase_events.size(); i += 6) {
+    MOE_HIP(hipEventSynchronize(c->phase_events[i + 5]));
+    for (int p = 0; p < 5; ++p) {
+      float ms = 0.f;
+      MOE_HIP(hipEventElapsedTime(&ms, c->phase_events[i + p], c->phase_events[i + p + 1]));
+      c->phase_ms[p] += ms;
+    }
+    c->phase_layers += 1;
+  }
+  for (hipEvent_t e : c->phase_events) c->phase_free.push_back(e);
+  c->phase_events.clear();
+  out->route_ms = c->phase_ms[0];
+  out->permute_ms = c->phase_ms[1];
+  out->gate_up_ms = c->phase_ms[2];
+  out->down_ms = c->phase_ms[3];
+  out->combine_ms = c->phase_ms[4];
+  out->n_layers = c->phase_layers;
+  if (reset) {
+    for (double& v : c->phase_ms) v = 0.0;
+    c->phase_layers = 0;
+  }
   return MOE_OK;
 }

@@ -14,7 +14,6 @@ namespace moe {
 namespace {
 
 constexpr int kRouteWaves = 4;
-constexpr int kMaxEPerWave = MOE_MAX_E / kRouteWaves;  // 32
 
 template <typename T> struct Load8;
 
