@@ -223,6 +223,13 @@ moe_status moe_layer_forward(moe_ctx* ctx, const moe_shape* shape,
                              void* workspace, void* stream,
                              moe_layer_stats* stats);
 
+/* Stack glue (outside the block itself): weightless RMS normalisation of the
+ * residual stream, out[t,:] = X[t,:] / sqrt(mean_h X[t,h]^2 + eps), float32
+ * arithmetic, one rounding to the storage dtype.  A stack of MoE blocks is
+ * x_{l+1} = x_l + Block_l(rmsnorm(x_l)): call this, then moe_layer_forward
+ * with `residual` = x_l.  X, out [T,H] storage dtype (may not alias). */
+moe_status moe_rmsnorm(const moe_shape* shape, const void* X, void* out, float eps, void* stream);
+
 /* Host-side totals of the context's side stream since creation (or the last
  * reset): bytes copied and the summed duration of the copies as measured by
  * event pairs around each one.  Synchronises the side stream. */

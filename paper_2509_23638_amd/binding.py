@@ -87,16 +87,18 @@ _lib.moe_phase_timing.argtypes = [_P, C.c_int32]
 _lib.moe_phase_times_get.argtypes = [_P, C.POINTER(moe_phase_times), C.c_int32]
 _lib.moe_probe_copy.argtypes = [_P, _P, C.c_size_t, _P]
 _lib.moe_probe_read.argtypes = [_P, C.c_size_t, _P, _P]
+_lib.moe_rmsnorm.argtypes = [_SH, _P, _P, C.c_float, _P]
 _lib.moe_workspace_views.argtypes = [_SH, _P] + [C.POINTER(_P)] * 7
 for _n in ("moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_create",
            "moe_destroy", "moe_layer_forward", "moe_stream_totals_get", "moe_workspace_views",
-           "moe_phase_timing", "moe_phase_times_get", "moe_probe_copy", "moe_probe_read"):
+           "moe_phase_timing", "moe_phase_times_get", "moe_probe_copy", "moe_probe_read",
+           "moe_rmsnorm"):
     getattr(_lib, _n).restype = C.c_int32
 
 EXPORTS = ["moe_version", "moe_last_error", "moe_workspace_bytes", "moe_route", "moe_permute",
            "moe_grouped_ffn", "moe_combine", "moe_create", "moe_destroy", "moe_layer_forward",
            "moe_stream_totals_get", "moe_workspace_views", "moe_phase_timing",
-           "moe_phase_times_get", "moe_probe_copy", "moe_probe_read"]
+           "moe_phase_times_get", "moe_probe_copy", "moe_probe_read", "moe_rmsnorm"]
 
 
 def _check(st: int):
@@ -309,6 +311,13 @@ def moe_layer_forward(ctx: Context, shape, layer: Layer, X, out, workspace, resi
         _ptr(workspace, "workspace", (torch.uint8,), moe_workspace_bytes(shape)),
         _stream(stream), C.byref(stats) if stats is not None else None))
     return stats.as_dict() if stats is not None else None
+
+
+def moe_rmsnorm(shape, X, out, eps=1e-6, stream=None):
+    sd = _storage_dtypes(shape)
+    n = shape.T * shape.H
+    _check(_lib.moe_rmsnorm(C.byref(shape), _ptr(X, "X", sd, n), _ptr(out, "out", sd, n),
+                            C.c_float(eps), _stream(stream)))
 
 
 def moe_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None):

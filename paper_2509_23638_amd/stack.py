@@ -1,0 +1,104 @@
+"""Driver of a stack of MoE blocks with streamed experts (argument marshalling
+and call sequencing only; the arithmetic is in the library's kernels).
+
+x_{l+1} = x_l + Block_l(rmsnorm(x_l)).  Per layer a residency mask says which
+routed experts live in device memory; the others live in pinned host memory and
+reach the GPU through the context's slots, either prefetched one layer ahead
+(mask supplied by the caller) or on demand.
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def _to_torch(a: np.ndarray) -> torch.Tensor:
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16)
+    return torch.from_numpy(a)
+
+
+class StreamedStack:
+    def __init__(self, shape: B.moe_shape, layers_host: Sequence[dict],
+                 resident_masks: Sequence[Sequence[bool]], n_ondemand_slots=2,
+                 n_prefetch_slots_per_group=2, n_layers: Optional[int] = None):
+        """layers_host: dicts with numpy Wr, b, Wg, Wu, Wd ([E+S, ...]).  If
+        ``n_layers`` exceeds len(layers_host) the weights repeat with that
+        period (each layer still has its own id, mask and slot traffic)."""
+        self.shape = shape
+        self.n_layers = n_layers or len(layers_host)
+        self.ctx = B.Context(shape, n_ondemand_slots, n_prefetch_slots_per_group)
+        self.ws = B.alloc_workspace(shape)
+        self.resident = [list(m) for m in resident_masks]
+        E, S = shape.E, shape.S
+        P = len(layers_host)
+        # one device / pinned copy per (weight period, expert), chosen by the
+        # union of what the layers sharing those weights need
+        need_dev = [[False] * (E + S) for _ in range(P)]
+        need_pin = [[False] * (E + S) for _ in range(P)]
+        for l in range(self.n_layers):
+            for e in range(E + S):
+                res = e >= E or self.resident[l][e]
+                (need_dev if res else need_pin)[l % P][e] = True
+        self._dev, self._pin, self._router = [], [], []
+        for p, L in enumerate(layers_host):
+            dev = {n: [None] * (E + S) for n in ("Wg", "Wu", "Wd")}
+            pin = {n: [None] * (E + S) for n in ("Wg", "Wu", "Wd")}
+            for e in range(E + S):
+                for n in ("Wg", "Wu", "Wd"):
+                    t = _to_torch(L[n][e])
+                    if need_dev[p][e]:
+                        dev[n][e] = t.cuda()
+                    if need_pin[p][e]:
+                        h = torch.empty(t.shape, dtype=t.dtype, pin_memory=True)
+                        h.copy_(t)
+                        pin[n][e] = h
+            self._dev.append(dev)
+            self._pin.append(pin)
+            self._router.append((_to_torch(L["Wr"]).cuda(), _to_torch(L["b"]).cuda()))
+        self.layers: List[B.Layer] = []
+        for l in range(self.n_layers):
+            p = l % P
+            d, h = self._dev[p], self._pin[p]
+            self.layers.append(B.make_layer_desc(
+                shape, self._router[p][0], self._router[p][1],
+                dev=(d["Wg"], d["Wu"], d["Wd"]), pinned=(h["Wg"], h["Wu"], h["Wd"]), layer_id=l))
+        self._norm = None
+
+    def close(self):
+        self.ctx.close()
+
+    def layer_forward(self, l: int, x_in: torch.Tensor, out: torch.Tensor, residual=None,
+                      prefetch_next_mask=None, next_l: Optional[int] = None, want_stats=True):
+        """One block on an already normalised input."""
+        nl = self.layers[next_l] if next_l is not None else None
+        return B.moe_layer_forward(self.ctx, self.shape, self.layers[l], x_in, out, self.ws,
+                                   resident_mask=self.resident[l], next_layer=nl,
+                                   prefetch_next_mask=prefetch_next_mask, residual=residual,
+                                   want_stats=want_stats)
+
+    def step(self, X: torch.Tensor, prefetch_masks: Optional[Sequence] = None,
+             wrap_prefetch: bool = False, want_stats=True):
+        """One pass of the residual stream through all layers.  prefetch_masks[l]
+        (or None) names the experts of layer l+1 to start copying while layer l
+        computes; with ``wrap_prefetch`` the last entry targets layer 0 of the
+        next step.  Returns (x_final, list of per-layer stats)."""
+        if self._norm is None or self._norm.shape != X.shape:
+            self._norm = torch.empty_like(X)
+            self._bufs = [torch.empty_like(X), torch.empty_like(X)]
+        x = X
+        stats = []
+        for l in range(self.n_layers):
+            B.moe_rmsnorm(self.shape, x, self._norm)
+            out = self._bufs[l & 1]
+            nxt = l + 1 if l + 1 < self.n_layers else (0 if wrap_prefetch else None)
+            pm = prefetch_masks[l] if (prefetch_masks is not None and nxt is not None) else None
+            stats.append(self.layer_forward(l, self._norm, out, residual=x, prefetch_next_mask=pm,
+                                            next_l=nxt if pm is not None else None,
+                                            want_stats=want_stats))
+            x = out
+        return x, stats
