@@ -240,6 +240,20 @@ typedef struct {
 } moe_stream_totals;
 moe_status moe_stream_totals_get(moe_ctx* ctx, moe_stream_totals* out, int32_t reset);
 
+/* Context options.
+ * MOE_OPT_SYNC_COPIES (default 0): with a non-zero value every expert copy
+ *   waits for the compute stream to drain first and is waited for before
+ *   anything else is queued, i.e. no copy overlaps any compute (the
+ *   "synchronous loading" Section 4.4 compares against).  A control for
+ *   measurements; results are unchanged.
+ * MOE_OPT_COPY_SPLIT (default 1): 1 = an expert whose three matrices are
+ *   contiguous in pinned host memory (Wu = Wg + H*F elements, Wd = Wu + H*F)
+ *   moves as one copy; 3 = one copy per matrix in need order (gate, up, down)
+ *   with the first FFN phase gated on gate+up only (Section 4.4's sub-tensor
+ *   granularity).  Non-contiguous experts always move as three copies. */
+typedef enum { MOE_OPT_SYNC_COPIES = 0, MOE_OPT_COPY_SPLIT = 1 } moe_option;
+moe_status moe_set_option(moe_ctx* ctx, int32_t option, int64_t value);
+
 /* Optional per-phase timing of layers whose experts are all resident: when
  * enabled, moe_layer_forward records an event on `stream` before the router
  * and after each of the five kernels (route, permute, gate/up, down, combine);

@@ -16,6 +16,7 @@ import torch
 from .build import LIB
 
 MOE_F32, MOE_BF16 = 0, 1
+MOE_OPT_SYNC_COPIES, MOE_OPT_COPY_SPLIT = 0, 1
 STATUS = {0: "MOE_OK", -1: "MOE_ERR_INVALID_ARG", -2: "MOE_ERR_UNSUPPORTED",
           -3: "MOE_ERR_WORKSPACE", -4: "MOE_ERR_HIP", -5: "MOE_ERR_SLOT_EXHAUSTED"}
 
@@ -87,18 +88,20 @@ _lib.moe_phase_timing.argtypes = [_P, C.c_int32]
 _lib.moe_phase_times_get.argtypes = [_P, C.POINTER(moe_phase_times), C.c_int32]
 _lib.moe_probe_copy.argtypes = [_P, _P, C.c_size_t, _P]
 _lib.moe_probe_read.argtypes = [_P, C.c_size_t, _P, _P]
+_lib.moe_set_option.argtypes = [_P, C.c_int32, C.c_int64]
 _lib.moe_rmsnorm.argtypes = [_SH, _P, _P, C.c_float, _P]
 _lib.moe_workspace_views.argtypes = [_SH, _P] + [C.POINTER(_P)] * 7
 for _n in ("moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_create",
            "moe_destroy", "moe_layer_forward", "moe_stream_totals_get", "moe_workspace_views",
            "moe_phase_timing", "moe_phase_times_get", "moe_probe_copy", "moe_probe_read",
-           "moe_rmsnorm"):
+           "moe_rmsnorm", "moe_set_option"):
     getattr(_lib, _n).restype = C.c_int32
 
 EXPORTS = ["moe_version", "moe_last_error", "moe_workspace_bytes", "moe_route", "moe_permute",
            "moe_grouped_ffn", "moe_combine", "moe_create", "moe_destroy", "moe_layer_forward",
            "moe_stream_totals_get", "moe_workspace_views", "moe_phase_timing",
-           "moe_phase_times_get", "moe_probe_copy", "moe_probe_read", "moe_rmsnorm"]
+           "moe_phase_times_get", "moe_probe_copy", "moe_probe_read", "moe_rmsnorm",
+           "moe_set_option"]
 
 
 def _check(st: int):
@@ -251,6 +254,12 @@ class Context:
             self.close()
         except Exception:
             pass
+
+    def set_sync_copies(self, enable: bool):
+        _check(_lib.moe_set_option(self._h, MOE_OPT_SYNC_COPIES, 1 if enable else 0))
+
+    def set_copy_split(self, n: int):
+        _check(_lib.moe_set_option(self._h, MOE_OPT_COPY_SPLIT, n))
 
     def phase_timing(self, enable: bool):
         _check(_lib.moe_phase_timing(self._h, 1 if enable else 0))

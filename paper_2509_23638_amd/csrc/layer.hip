@@ -28,12 +28,21 @@ struct Slot {
   int expert = -1;
   bool valid = false;        // holds (or is receiving) `expert` of `layer_id`
   bool has_release = false;  // `released` has been recorded at least once
-  hipEvent_t copied_gu = nullptr, copied_d = nullptr, released = nullptr;
+  hipEvent_t copied = nullptr;     // borrowed from the copy record; NULL = bytes have landed
+  bool gu_pending = false;         // `copied_gu` was recorded for the copy in flight
+  hipEvent_t copied_gu = nullptr;  // owned: gate and up projections have landed
+  hipEvent_t released = nullptr;   // owned: last reader on the compute stream is done
 };
 
-struct TimedCopy {
-  hipEvent_t start, stop;
-  int64_t bytes;
+// One expert copy on the side stream.  `done` is recorded right after the
+// bytes and doubles as the gate for the compute stream and as the end of the
+// timed interval.  Back-to-back copies do not record a start marker of their
+// own (every marker is a bubble on the link): their interval starts at the
+// previous copy's `done`.
+struct CopyRec {
+  hipEvent_t start = nullptr;  // owned, or NULL when the interval starts at the previous `done`
+  hipEvent_t done = nullptr;   // owned
+  int64_t bytes = 0;
 };
 
 }  // namespace
@@ -50,10 +59,15 @@ struct moe_ctx {
   hipStream_t copy_stream = nullptr;
   hipEvent_t ev_counts = nullptr;
   int32_t* host_counts = nullptr;  // pinned, MOE_MAX_E ints
-  std::vector<moe::TimedCopy> pending;    // recorded, not yet harvested
-  std::vector<moe::TimedCopy> free_pairs; // reusable event pairs
+  std::vector<moe::CopyRec> pending;   // queued copies in stream order, oldest first
+  hipEvent_t held_done = nullptr;      // `done` of the newest harvested copy (the next
+                                       // record may start its interval there)
+  std::vector<hipEvent_t> free_events; // timing-enabled, reusable
   int64_t tot_bytes = 0, tot_copies = 0;
   double tot_ms = 0.0;
+  bool sync_copies = false;  // control run: no copy/compute overlap at all
+  int copy_split = 1;        // 1: one copy per expert when its matrices are contiguous on the
+                             // host; 3: one copy per matrix, first phase gated on gate+up only
   // optional per-phase timing of all-resident layers (6 boundary events each)
   bool phase_timing = false;
   std::vector<hipEvent_t> phase_events;  // 6 per timed layer, in call order
@@ -68,7 +82,6 @@ namespace {
 moe_status make_slot(Slot& s, size_t bytes) {
   MOE_HIP(hipMalloc(reinterpret_cast<void**>(&s.mem), bytes));
   MOE_HIP(hipEventCreateWithFlags(&s.copied_gu, hipEventDisableTiming));
-  MOE_HIP(hipEventCreateWithFlags(&s.copied_d, hipEventDisableTiming));
   MOE_HIP(hipEventCreateWithFlags(&s.released, hipEventDisableTiming));
   return MOE_OK;
 }
@@ -76,66 +89,117 @@ moe_status make_slot(Slot& s, size_t bytes) {
 void drop_slot(Slot& s) {
   if (s.mem) (void)hipFree(s.mem);
   if (s.copied_gu) (void)hipEventDestroy(s.copied_gu);
-  if (s.copied_d) (void)hipEventDestroy(s.copied_d);
   if (s.released) (void)hipEventDestroy(s.released);
   s = Slot();
 }
 
+// A completed `done` event goes back to the pool: no slot may keep gating on it.
+void recycle_done(moe_ctx* c, hipEvent_t ev) {
+  if (!ev) return;
+  auto clear = [&](std::vector<Slot>& v) {
+    for (Slot& sl : v)
+      if (sl.copied == ev) {
+        sl.copied = nullptr;
+        sl.gu_pending = false;
+      }
+  };
+  clear(c->ondemand);
+  clear(c->prefetch[0]);
+  clear(c->prefetch[1]);
+  c->free_events.push_back(ev);
+}
+
+// Account for finished copies, oldest first (one stream: they finish in order).
 moe_status harvest(moe_ctx* c, bool wait) {
-  size_t keep = 0;
-  for (size_t i = 0; i < c->pending.size(); ++i) {
-    TimedCopy& t = c->pending[i];
-    hipError_t q = wait ? hipEventSynchronize(t.stop) : hipEventQuery(t.stop);
-    if (q == hipSuccess) {
-      float ms = 0.f;
-      MOE_HIP(hipEventElapsedTime(&ms, t.start, t.stop));
-      c->tot_ms += ms;
-      c->tot_bytes += t.bytes;
-      c->tot_copies += 1;
-      c->free_pairs.push_back(t);
-    } else if (q == hipErrorNotReady) {
-      c->pending[keep++] = t;
-    } else {
-      return fail(MOE_ERR_HIP, "event query: %s", hipGetErrorString(q));
-    }
+  size_t n = 0;
+  for (; n < c->pending.size(); ++n) {
+    CopyRec& r = c->pending[n];
+    hipError_t q = wait ? hipEventSynchronize(r.done) : hipEventQuery(r.done);
+    if (q == hipErrorNotReady) break;
+    if (q != hipSuccess) return fail(MOE_ERR_HIP, "event query: %s", hipGetErrorString(q));
+    float ms = 0.f;
+    hipEvent_t from = r.start ? r.start : c->held_done;
+    if (from) MOE_HIP(hipEventElapsedTime(&ms, from, r.done));
+    c->tot_ms += ms;
+    c->tot_bytes += r.bytes;
+    c->tot_copies += 1;
+    if (r.start) c->free_events.push_back(r.start);
+    recycle_done(c, c->held_done);
+    c->held_done = r.done;
   }
-  c->pending.resize(keep);
+  c->pending.erase(c->pending.begin(), c->pending.begin() + n);
   return MOE_OK;
 }
 
-moe_status timed_pair(moe_ctx* c, TimedCopy* out) {
-  if (c->free_pairs.empty() && c->pending.size() >= 64) {
+moe_status timing_event(moe_ctx* c, hipEvent_t* out) {
+  if (c->free_events.empty() && c->pending.size() >= 32) {
     moe_status st = harvest(c, false);
     if (st != MOE_OK) return st;
   }
-  if (!c->free_pairs.empty()) {
-    *out = c->free_pairs.back();
-    c->free_pairs.pop_back();
+  if (!c->free_events.empty()) {
+    *out = c->free_events.back();
+    c->free_events.pop_back();
     return MOE_OK;
   }
-  MOE_HIP(hipEventCreate(&out->start));
-  MOE_HIP(hipEventCreate(&out->stop));
+  MOE_HIP(hipEventCreate(out));
   return MOE_OK;
 }
 
 // Queue the copy of one expert into `slot` on the side stream.
 moe_status queue_copy(moe_ctx* c, const moe_shape& s, Slot& slot, const moe_expert_ptrs& src,
-                      uint64_t layer_id, int expert) {
+                      uint64_t layer_id, int expert, hipStream_t compute) {
   const size_t mb = (size_t)s.H * s.F * elem_size(s);
-  if (slot.has_release) MOE_HIP(hipStreamWaitEvent(c->copy_stream, slot.released, 0));
-  TimedCopy tc;
-  moe_status st = timed_pair(c, &tc);
+  if (c->sync_copies) MOE_HIP(hipStreamSynchronize(compute));
+  bool waited = false;
+  if (slot.has_release) {
+    // only put a wait on the link's queue if the last reader is really still running
+    const hipError_t q = hipEventQuery(slot.released);
+    if (q == hipErrorNotReady) {
+      MOE_HIP(hipStreamWaitEvent(c->copy_stream, slot.released, 0));
+      waited = true;
+    } else if (q != hipSuccess) {
+      return fail(MOE_ERR_HIP, "event query: %s", hipGetErrorString(q));
+    }
+  }
+  CopyRec rec;
+  rec.bytes = (int64_t)(3 * mb);
+  moe_status st = timing_event(c, &rec.done);
   if (st != MOE_OK) return st;
-  tc.bytes = (int64_t)(3 * mb);
-  MOE_HIP(hipEventRecord(tc.start, c->copy_stream));
-  // need order: the first FFN phase reads gate and up, the second reads down
-  MOE_HIP(hipMemcpyAsync(slot.mem, src.Wg, mb, hipMemcpyHostToDevice, c->copy_stream));
-  MOE_HIP(hipMemcpyAsync(slot.mem + mb, src.Wu, mb, hipMemcpyHostToDevice, c->copy_stream));
-  MOE_HIP(hipEventRecord(slot.copied_gu, c->copy_stream));
-  MOE_HIP(hipMemcpyAsync(slot.mem + 2 * mb, src.Wd, mb, hipMemcpyHostToDevice, c->copy_stream));
-  MOE_HIP(hipEventRecord(slot.copied_d, c->copy_stream));
-  MOE_HIP(hipEventRecord(tc.stop, c->copy_stream));
-  c->pending.push_back(tc);
+  // back to back with a copy that is still in flight: the interval starts at its `done`
+  bool chained = !waited && !c->sync_copies && !c->pending.empty();
+  if (chained) {
+    const hipError_t q = hipEventQuery(c->pending.back().done);
+    chained = q == hipErrorNotReady;
+  }
+  if (!chained) {
+    // the link was (or may be) idle: drain the bookkeeping so that no later
+    // record borrows a stale `done`, then mark the start explicitly
+    st = harvest(c, false);
+    if (st != MOE_OK) return st;
+    st = timing_event(c, &rec.start);
+    if (st != MOE_OK) return st;
+    MOE_HIP(hipEventRecord(rec.start, c->copy_stream));
+  }
+  const char* g = static_cast<const char*>(src.Wg);
+  const bool contiguous = static_cast<const char*>(src.Wu) == g + mb &&
+                          static_cast<const char*>(src.Wd) == g + 2 * mb;
+  slot.gu_pending = false;
+  if (c->copy_split == 1 && contiguous) {
+    MOE_HIP(hipMemcpyAsync(slot.mem, src.Wg, 3 * mb, hipMemcpyHostToDevice, c->copy_stream));
+  } else {
+    // need order: the first FFN phase reads gate and up, the second reads down
+    MOE_HIP(hipMemcpyAsync(slot.mem, src.Wg, mb, hipMemcpyHostToDevice, c->copy_stream));
+    MOE_HIP(hipMemcpyAsync(slot.mem + mb, src.Wu, mb, hipMemcpyHostToDevice, c->copy_stream));
+    if (c->copy_split == 3) {
+      MOE_HIP(hipEventRecord(slot.copied_gu, c->copy_stream));
+      slot.gu_pending = true;
+    }
+    MOE_HIP(hipMemcpyAsync(slot.mem + 2 * mb, src.Wd, mb, hipMemcpyHostToDevice, c->copy_stream));
+  }
+  MOE_HIP(hipEventRecord(rec.done, c->copy_stream));
+  c->pending.push_back(rec);
+  if (c->sync_copies) MOE_HIP(hipStreamSynchronize(c->copy_stream));
+  slot.copied = rec.done;
   slot.layer_id = layer_id;
   slot.expert = expert;
   slot.valid = true;
@@ -212,8 +276,12 @@ extern "C" moe_status moe_destroy(moe_ctx* c) {
   for (auto& s : c->ondemand) moe::drop_slot(s);
   for (int g = 0; g < 2; ++g)
     for (auto& s : c->prefetch[g]) moe::drop_slot(s);
-  for (auto& t : c->pending) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
-  for (auto& t : c->free_pairs) { (void)hipEventDestroy(t.start); (void)hipEventDestroy(t.stop); }
+  for (auto& r : c->pending) {
+    if (r.start) (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.done);
+  }
+  if (c->held_done) (void)hipEventDestroy(c->held_done);
+  for (auto& e : c->free_events) (void)hipEventDestroy(e);
   for (auto& e : c->phase_events) (void)hipEventDestroy(e);
   for (auto& e : c->phase_free) (void)hipEventDestroy(e);
   if (c->ev_counts) (void)hipEventDestroy(c->ev_counts);
@@ -375,7 +443,8 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
       GroupList one;
       one.n = 1;
       one.id[0] = (uint8_t)e;
-      st = launch_ffn_gated(s, X, perm, offset, tab, one, Y, h, stream, sl.copied_gu, sl.copied_d, nullptr);
+      st = launch_ffn_gated(s, X, perm, offset, tab, one, Y, h, stream,
+                            sl.gu_pending ? sl.copied_gu : sl.copied, sl.copied, nullptr);
       if (st != MOE_OK) return st;
       MOE_HIP(hipEventRecord(sl.released, stream));
       sl.has_release = true;
@@ -384,7 +453,7 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
     for (int e : misses) {
       Slot& sl = c->ondemand[c->od_next];
       c->od_next = (c->od_next + 1) % (int)c->ondemand.size();
-      st = queue_copy(c, s, sl, layer->host_pinned[e], layer->layer_id, e);
+      st = queue_copy(c, s, sl, layer->host_pinned[e], layer->layer_id, e, stream);
       if (st != MOE_OK) return st;
       tab.Wg[e] = sl.mem;
       tab.Wu[e] = sl.mem + mb;
@@ -392,7 +461,8 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
       GroupList one;
       one.n = 1;
       one.id[0] = (uint8_t)e;
-      st = launch_ffn_gated(s, X, perm, offset, tab, one, Y, h, stream, sl.copied_gu, sl.copied_d, nullptr);
+      st = launch_ffn_gated(s, X, perm, offset, tab, one, Y, h, stream,
+                            sl.gu_pending ? sl.copied_gu : sl.copied, sl.copied, nullptr);
       if (st != MOE_OK) return st;
       MOE_HIP(hipEventRecord(sl.released, stream));
       sl.has_release = true;
@@ -425,7 +495,7 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
       if (!bit(host_prefetch_next_mask, e)) continue;
       const moe_expert_ptrs& src = next_layer->host_pinned[e];
       MOE_REQUIRE(src.Wg && src.Wu && src.Wd, "moe_layer_forward: prefetch of expert %d without a pinned copy", e);
-      st = queue_copy(c, s, nxt[used], src, next_layer->layer_id, e);
+      st = queue_copy(c, s, nxt[used], src, next_layer->layer_id, e, stream);
       if (st != MOE_OK) return st;
       ++used;
       if (stats) {
@@ -436,6 +506,21 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
   }
   c->cur_group ^= 1;
   return MOE_OK;
+}
+
+extern "C" moe_status moe_set_option(moe_ctx* c, int32_t option, int64_t value) {
+  MOE_REQUIRE(c, "moe_set_option: NULL context");
+  switch (option) {
+    case MOE_OPT_SYNC_COPIES:
+      c->sync_copies = value != 0;
+      return MOE_OK;
+    case MOE_OPT_COPY_SPLIT:
+      MOE_REQUIRE(value == 1 || value == 3, "moe_set_option: copy split must be 1 or 3");
+      c->copy_split = (int)value;
+      return MOE_OK;
+    default:
+      return moe::fail(MOE_ERR_INVALID_ARG, "moe_set_option: unknown option %d", option);
+  }
 }
 
 extern "C" moe_status moe_phase_timing(moe_ctx* c, int32_t enable) {

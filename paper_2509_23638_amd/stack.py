@@ -49,14 +49,17 @@ class StreamedStack:
             dev = {n: [None] * (E + S) for n in ("Wg", "Wu", "Wd")}
             pin = {n: [None] * (E + S) for n in ("Wg", "Wu", "Wd")}
             for e in range(E + S):
-                for n in ("Wg", "Wu", "Wd"):
-                    t = _to_torch(L[n][e])
-                    if need_dev[p][e]:
+                ts = [_to_torch(L[n][e]) for n in ("Wg", "Wu", "Wd")]
+                if need_dev[p][e]:
+                    for n, t in zip(("Wg", "Wu", "Wd"), ts):
                         dev[n][e] = t.cuda()
-                    if need_pin[p][e]:
-                        h = torch.empty(t.shape, dtype=t.dtype, pin_memory=True)
-                        h.copy_(t)
-                        pin[n][e] = h
+                if need_pin[p][e]:
+                    # the three matrices back to back: one copy moves the expert
+                    blk = torch.empty(3 * ts[0].numel(), dtype=ts[0].dtype, pin_memory=True)
+                    for i, (n, t) in enumerate(zip(("Wg", "Wu", "Wd"), ts)):
+                        v = blk[i * t.numel():(i + 1) * t.numel()].view(t.shape)
+                        v.copy_(t)
+                        pin[n][e] = v
             self._dev.append(dev)
             self._pin.append(pin)
             self._router.append((_to_torch(L["Wr"]).cuda(), _to_torch(L["b"]).cuda()))
@@ -102,3 +105,23 @@ class StreamedStack:
                                             want_stats=want_stats))
             x = out
         return x, stats
+
+
+def noisy_topk_prefetch_mask(next_logits: np.ndarray, noise: np.ndarray, k: int, n_prefetch: int,
+                             resident: Sequence[bool]) -> np.ndarray:
+    """Harness-side stand-in for an expert predictor (not part of the block):
+    rank the next layer's experts by how many tokens have them in the top-k of
+    (true logits + noise) and pick the ``n_prefetch`` best non-resident ones
+    that got any vote; ties go to the lower index."""
+    noisy = np.asarray(next_logits, dtype=np.float64) + np.asarray(noise, dtype=np.float64)
+    E = noisy.shape[1]
+    order = np.argsort(-noisy, axis=1, kind="stable")[:, :k]
+    votes = np.bincount(order.reshape(-1), minlength=E)
+    ranked = sorted(range(E), key=lambda e: (-int(votes[e]), e))
+    mask = np.zeros(E, dtype=bool)
+    for e in ranked:
+        if mask.sum() >= n_prefetch:
+            break
+        if not resident[e] and votes[e] > 0:
+            mask[e] = True
+    return mask

@@ -58,3 +58,23 @@ def test_host_side_argument_checks(lib):
     # f32 storage has the looser multiple-of-8 rule
     assert B.moe_workspace_bytes(B.make_shape(4, 72, 4, 2, 40, dtype="f32")) > 0
     assert B.moe_version().startswith("moe_hotpath")
+
+
+def test_harness_prefetch_mask_matches_oracle_reading(lib):
+    """The harness-side predictor stand-in and the oracle's statement of the
+    same reading are written separately; they must pick the same experts."""
+    import numpy as np
+    import oracle.moe_oracle as O
+    from paper_2509_23638_amd.stack import noisy_topk_prefetch_mask
+    r = np.random.Generator(np.random.PCG64(17))
+    for trial in range(40):
+        E = int(r.integers(4, 20))
+        T = int(r.integers(1, 30))
+        k = int(r.integers(1, min(E, 6) + 1))
+        lg = r.integers(-3, 4, size=(T, E)).astype(np.float64)        # ties on purpose
+        noise = r.integers(-1, 2, size=(T, E)).astype(np.float64)
+        res = r.random(E) < 0.5
+        n = int(r.integers(0, 4))
+        a = noisy_topk_prefetch_mask(lg, noise, k, n, res)
+        b = O.predicted_prefetch_set(lg, noise, k, n, res)
+        assert np.array_equal(a, b)
