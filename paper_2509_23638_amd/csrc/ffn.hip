@@ -25,6 +25,8 @@
 // of a row block), for the small full-precision configuration.
 #include "common.h"
 
+#include <stdlib.h>
+
 namespace moe {
 namespace {
 
@@ -36,10 +38,11 @@ constexpr int kThreads = kWaves * MOE_WAVE;
 constexpr int kKStep = 32;          // contraction depth of one MFMA
 constexpr int kStepsPerChunk = 4;   // k-steps staged per LDS buffer
 constexpr int kChunk = kKStep * kStepsPerChunk;  // 128
-constexpr int kMaxTiles = 4;        // 16-row activation tiles per pass
-constexpr int kTokBlock = 16 * kMaxTiles;        // 64 bucket rows per block
 constexpr int kFragBytes = MOE_WAVE * 16;        // one B fragment in LDS
-constexpr int kBufBytes = kMaxTiles * kStepsPerChunk * kFragBytes;  // 16 KiB
+// TB = 16-row activation tiles per pass: 4 (64 bucket rows) at decode sizes,
+// 8 (128 rows) when experts see more rows, so that an expert's weights are
+// still read once.  One LDS buffer holds TB * 4 fragments.
+constexpr int buf_bytes(int tb) { return tb * kStepsPerChunk * kFragBytes; }
 
 enum { kGateUp = 0, kDown = 1 };
 
@@ -55,8 +58,9 @@ struct FfnArgs {
 
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
 
-template <int MODE, int NT>
+template <int MODE, int NT, int TB>
 struct Streamer {
+  static constexpr int kBufBytes = buf_bytes(TB);
   const FfnArgs& a;
   const uint16_t* w0;     // this lane's first element in tile 0
   const uint16_t* w1;     // ... in tile 1
@@ -141,11 +145,11 @@ struct Streamer {
 
 // One workgroup: expert `e`, output rows [n0, n0 + rows per WG), bucket rows
 // [r0, min(r0 + 64, row_end)).
-template <int MODE, int NT>
+template <int MODE, int NT, int TB>
 __device__ __forceinline__ void ffn_block(const FfnArgs& a, const uint16_t* W0, const uint16_t* W1,
                                           int n0, int r0, int row_end, int shared_base,
                                           unsigned char* lds) {
-  Streamer<MODE, NT> st(a);
+  Streamer<MODE, NT, TB> st(a);
   st.lds = lds;
   st.lane = threadIdx.x & (MOE_WAVE - 1);
   st.wave = threadIdx.x / MOE_WAVE;
@@ -193,10 +197,11 @@ __device__ __forceinline__ void ffn_block(const FfnArgs& a, const uint16_t* W0, 
   }
 }
 
-template <int MODE>
+template <int MODE, int TB>
 __global__ __launch_bounds__(kThreads) void ffn_stream_kernel(FfnArgs a, ExpertTable tab,
                                                               GroupList groups) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * kBufBytes];
+  constexpr int kTokBlock = 16 * TB;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * buf_bytes(TB)];
   const int e = groups.id[blockIdx.y];
   int row_begin, row_end, shared_base = -1;
   if (e < a.E) {
@@ -220,12 +225,145 @@ __global__ __launch_bounds__(kThreads) void ffn_stream_kernel(FfnArgs a, ExpertT
     W0 = W1 = static_cast<const uint16_t*>(tab.Wd[e]);
     n0 = blockIdx.x * (kWaves * 32);
   }
-  switch (nt) {
-    case 1: ffn_block<MODE, 1>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
-    case 2: ffn_block<MODE, 2>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
-    case 3: ffn_block<MODE, 3>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
-    default: ffn_block<MODE, 4>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
+  // rows past the bucket's end are clamped on load and dropped on store, so a
+  // larger tile count than needed is only wasted arithmetic
+  if (TB <= 4) {
+    switch (nt) {
+      case 1: ffn_block<MODE, 1, TB>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
+      case 2: ffn_block<MODE, 2, TB>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
+      case 3: ffn_block<MODE, 3, TB>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
+      default: ffn_block<MODE, 4, TB>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
+    }
+  } else {
+    if (nt <= 2) ffn_block<MODE, 2, TB>(a, W0, W1, n0, r0, row_end, shared_base, lds);
+    else if (nt <= 4) ffn_block<MODE, 4, TB>(a, W0, W1, n0, r0, row_end, shared_base, lds);
+    else if (nt <= 6) ffn_block<MODE, 6, TB>(a, W0, W1, n0, r0, row_end, shared_base, lds);
+    else ffn_block<MODE, TB, TB>(a, W0, W1, n0, r0, row_end, shared_base, lds);
   }
+}
+
+// ------------------------------------------------------- down, split-K ----
+// Down projection for few rows per expert (decode): the four wavefronts of a
+// workgroup share the same 32 weight rows and each walks a quarter of the
+// contraction, so a Mixtral-shaped layer has 128 x E workgroups instead of
+// 32 x E and the chip stays full even with two active experts.  No wave needs
+// another wave's activations, so the B fragments go from global memory (h is a
+// few MB and lives in L2) straight to registers: no LDS and no barrier in the
+// loop.  The four partial accumulators meet in LDS once, summed in wave order.
+template <int NT>
+struct SplitKStreamer {
+  const uint16_t* w0;
+  const uint16_t* w1;
+  const uint16_t* b[NT];  // this lane's activation row (at its k-group) per tile
+  bf16x8 wreg[2][kStepsPerChunk][2];
+  bf16x8 breg[2][NT][kStepsPerChunk];
+  f32x4 acc0[NT], acc1[NT];
+
+  template <int SET>
+  __device__ __forceinline__ void load(int c) {
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int s = 0; s < kStepsPerChunk; ++s)
+        breg[SET][t][s] = *reinterpret_cast<const bf16x8*>(b[t] + (size_t)c * kChunk + s * kKStep);
+#pragma unroll
+    for (int s = 0; s < kStepsPerChunk; ++s) {
+      wreg[SET][s][0] = *reinterpret_cast<const bf16x8*>(w0 + (size_t)c * kChunk + s * kKStep);
+      wreg[SET][s][1] = *reinterpret_cast<const bf16x8*>(w1 + (size_t)c * kChunk + s * kKStep);
+    }
+  }
+
+  template <int SET>
+  __device__ __forceinline__ void multiply() {
+#pragma unroll
+    for (int s = 0; s < kStepsPerChunk; ++s)
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        acc0[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[SET][s][0], breg[SET][t][s], acc0[t], 0, 0, 0);
+        acc1[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[SET][s][1], breg[SET][t][s], acc1[t], 0, 0, 0);
+      }
+  }
+
+  __device__ __forceinline__ void run(int cb, int ce) {
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      acc0[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+      acc1[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    if (cb >= ce) return;
+    load<0>(cb);
+    int c = cb;
+    for (; c + 1 < ce; c += 2) {
+      load<1>(c + 1);
+      multiply<0>();
+      if (c + 2 < ce) load<0>(c + 2);
+      multiply<1>();
+    }
+    if (c < ce) multiply<0>();
+  }
+};
+
+constexpr int kSplitRows = 32;   // weight rows per workgroup
+constexpr int kSplitTok = 32;    // bucket rows per pass (NT <= 2)
+
+template <int NT>
+__device__ __forceinline__ void down_splitk_block(const FfnArgs& a, const uint16_t* Wd, int n0,
+                                                  int r0, int row_end, float* red) {
+  const int lane = threadIdx.x & (MOE_WAVE - 1), wave = threadIdx.x / MOE_WAVE;
+  const int r = lane & 15, g = lane >> 4;
+  SplitKStreamer<NT> st;
+  st.w0 = Wd + (size_t)(n0 + r) * a.K + g * 8;
+  st.w1 = Wd + (size_t)(n0 + 16 + r) * a.K + g * 8;
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int p = min(r0 + t * 16 + r, row_end - 1);
+    st.b[t] = a.act + (size_t)p * a.K + g * 8;
+  }
+  const int nchunks = a.K / kChunk;
+  const int per = (nchunks + kWaves - 1) / kWaves;
+  st.run(min(wave * per, nchunks), min((wave + 1) * per, nchunks));
+
+  // partial sums -> LDS [wave][t][tile][lane] (float4), then a fixed-order sum
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    reinterpret_cast<f32x4*>(red)[((wave * NT + t) * 2 + 0) * MOE_WAVE + lane] = st.acc0[t];
+    reinterpret_cast<f32x4*>(red)[((wave * NT + t) * 2 + 1) * MOE_WAVE + lane] = st.acc1[t];
+  }
+  __syncthreads();
+  float* y = static_cast<float*>(a.out);
+  for (int q = wave; q < NT * 2; q += kWaves) {  // q = t * 2 + tile
+    const int t = q >> 1, tile = q & 1;
+    f32x4 sum = reinterpret_cast<const f32x4*>(red)[((0 * NT + t) * 2 + tile) * MOE_WAVE + lane];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) {
+      const f32x4 v = reinterpret_cast<const f32x4*>(red)[((w * NT + t) * 2 + tile) * MOE_WAVE + lane];
+      sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
+    }
+    const int p = r0 + t * 16 + r;
+    if (p < row_end)
+      *reinterpret_cast<float4*>(y + (size_t)p * a.N + n0 + tile * 16 + 4 * g) =
+          make_float4(sum[0], sum[1], sum[2], sum[3]);
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void ffn_down_splitk_kernel(FfnArgs a, ExpertTable tab,
+                                                                   GroupList groups) {
+  __shared__ __attribute__((aligned(16))) float red[kWaves * 2 * 2 * MOE_WAVE * 4];  // 16 KiB
+  const int e = groups.id[blockIdx.y];
+  int row_begin, row_end;
+  if (e < a.E) {
+    row_begin = a.offset[e];
+    row_end = a.offset[e + 1];
+  } else {
+    row_begin = a.A + (e - a.E) * a.T;
+    row_end = row_begin + a.T;
+  }
+  const int r0 = row_begin + blockIdx.z * kSplitTok;
+  if (r0 >= row_end) return;
+  const uint16_t* Wd = static_cast<const uint16_t*>(tab.Wd[e]);
+  const int n0 = blockIdx.x * kSplitRows;
+  if (row_end - r0 <= 16) down_splitk_block<1>(a, Wd, n0, r0, row_end, red);
+  else down_splitk_block<2>(a, Wd, n0, r0, row_end, red);
 }
 
 // ---------------------------------------------------------------- float32 --
@@ -293,6 +431,28 @@ __global__ __launch_bounds__(kThreads) void ffn_f32_kernel(F32Args a, ExpertTabl
 
 }  // namespace
 
+// The split-K down kernel pays off while an expert's bucket fits one 32-row
+// pass: expected rows per routed expert T*k/E (shared experts see T rows).
+// MOE_TUNE_DOWN=lds|splitk overrides the choice (for measurements).
+bool use_splitk_down(const moe_shape& s) {
+  static const char* env = getenv("MOE_TUNE_DOWN");
+  if (env && env[0] == 'l') return false;
+  if (env && env[0] == 's') return true;
+  const double rows = (double)s.T * s.k / s.E;
+  return rows <= 24.0 && (s.S == 0 || s.T <= 32);
+}
+
+// 128-row passes once an expert is expected to see more than 48 rows (or when
+// shared experts, which see every token, have more than 64).
+// MOE_TUNE_BLOCK=4|8 overrides the choice (for measurements).
+bool use_big_blocks(const moe_shape& s) {
+  static const char* env = getenv("MOE_TUNE_BLOCK");
+  if (env && env[0] == '4') return false;
+  if (env && env[0] == '8') return true;
+  const double rows = (double)s.T * s.k / s.E;
+  return rows > 48.0 || (s.S > 0 && s.T > 64);
+}
+
 // Phase 1 (gate and up projections, SiLU gate) for the experts in `groups`.
 moe_status launch_ffn_gate_up(const moe_shape& s, const void* X, const int32_t* perm,
                               const int32_t* offset, const ExpertTable& tab,
@@ -300,10 +460,14 @@ moe_status launch_ffn_gate_up(const moe_shape& s, const void* X, const int32_t* 
   if (groups.n == 0 || s.T == 0) return MOE_OK;
   const int A = s.T * s.k;
   if (s.dtype == MOE_BF16) {
-    const int tok_blocks = (s.T + kTokBlock - 1) / kTokBlock;
     FfnArgs gu{static_cast<const uint16_t*>(X), perm, offset, h, s.T, s.k, s.E, A, s.H, s.F};
-    hipLaunchKernelGGL((ffn_stream_kernel<kGateUp>), dim3(s.F / (kWaves * 16), groups.n, tok_blocks),
-                       dim3(kThreads), 0, stream, gu, tab, groups);
+    if (use_big_blocks(s)) {
+      hipLaunchKernelGGL((ffn_stream_kernel<kGateUp, 8>), dim3(s.F / (kWaves * 16), groups.n, (s.T + 127) / 128),
+                         dim3(kThreads), 0, stream, gu, tab, groups);
+    } else {
+      hipLaunchKernelGGL((ffn_stream_kernel<kGateUp, 4>), dim3(s.F / (kWaves * 16), groups.n, (s.T + 63) / 64),
+                         dim3(kThreads), 0, stream, gu, tab, groups);
+    }
   } else {
     const int zb = s.T < 64 ? s.T : 64;
     F32Args gu{static_cast<const float*>(X), perm, offset, static_cast<float*>(h),
@@ -322,10 +486,18 @@ moe_status launch_ffn_down(const moe_shape& s, const void* h, const int32_t* per
   if (groups.n == 0 || s.T == 0) return MOE_OK;
   const int A = s.T * s.k;
   if (s.dtype == MOE_BF16) {
-    const int tok_blocks = (s.T + kTokBlock - 1) / kTokBlock;
     FfnArgs dn{static_cast<const uint16_t*>(h), perm, offset, Y, s.T, s.k, s.E, A, s.F, s.H};
-    hipLaunchKernelGGL((ffn_stream_kernel<kDown>), dim3(s.H / (kWaves * 32), groups.n, tok_blocks),
-                       dim3(kThreads), 0, stream, dn, tab, groups);
+    if (use_splitk_down(s)) {
+      const int tok_blocks = (s.T + kSplitTok - 1) / kSplitTok;
+      hipLaunchKernelGGL(ffn_down_splitk_kernel, dim3(s.H / kSplitRows, groups.n, tok_blocks),
+                         dim3(kThreads), 0, stream, dn, tab, groups);
+    } else if (use_big_blocks(s)) {
+      hipLaunchKernelGGL((ffn_stream_kernel<kDown, 8>), dim3(s.H / (kWaves * 32), groups.n, (s.T + 127) / 128),
+                         dim3(kThreads), 0, stream, dn, tab, groups);
+    } else {
+      hipLaunchKernelGGL((ffn_stream_kernel<kDown, 4>), dim3(s.H / (kWaves * 32), groups.n, (s.T + 63) / 64),
+                         dim3(kThreads), 0, stream, dn, tab, groups);
+    }
   } else {
     const int zb = s.T < 64 ? s.T : 64;
     F32Args dn{static_cast<const float*>(h), perm, offset, Y, s.T, s.k, s.E, A, s.F, s.H};

@@ -2,99 +2,90 @@
 // counts the paper's scheduler sorts experts by (Section 4.3.2, Premise 1),
 // their exclusive scan, and the stable permutation the grouped FFN consumes.
 //
-// One workgroup of 16 wavefronts walks the A = T*k flat assignment ids in
-// tiles of 1024.  Pass 1 builds the histogram with LDS integer atomics; a
-// serial scan over <= 128 experts gives the offsets; pass 2 ranks every
-// assignment inside its wavefront with ballots (lanes of equal expert id),
-// stitches the wavefronts together through per-wave counts in LDS and writes
-// perm / inv_perm.  All integer work: the result is unique and bit-exact.
+// One workgroup per expert, so the experts' buckets are built in parallel on
+// different compute units with no hand-over between them: workgroup e scans all
+// A = T*k flat assignment ids (a few tens of KB, L2-resident), counting with
+// ballots how many name an expert below e (that is offset[e]) and how many
+// name e (count[e]); a second scan writes perm / inv_perm for the ids that
+// name e.  Each of the four wavefronts owns a contiguous quarter of the ids,
+// so ranks ascend with the id and the order inside a bucket is stable.  All
+// integer work: the result is unique and bit-exact.
 #include "common.h"
 
 namespace moe {
 namespace {
 
-constexpr int kPermThreads = 1024;
-constexpr int kPermWaves = kPermThreads / MOE_WAVE;
+constexpr int kPermWaves = 4;
+constexpr int kPermThreads = kPermWaves * MOE_WAVE;
+constexpr int kPermUnroll = 16;
 
 __global__ __launch_bounds__(kPermThreads) void permute_kernel(
     const int32_t* __restrict__ topk_idx, int32_t* __restrict__ count,
     int32_t* __restrict__ offset, int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm,
     int A, int E) {
-  __shared__ int s_hist[MOE_MAX_E];
-  __shared__ int s_base[MOE_MAX_E];               // next free position per expert
-  __shared__ int s_wave[kPermWaves][MOE_MAX_E];   // per-wave counts, then offsets
+  __shared__ int s_eq[kPermWaves], s_less[kPermWaves];
+  const int e = blockIdx.x;
+  const int lane = threadIdx.x & (MOE_WAVE - 1);
+  const int wave = threadIdx.x / MOE_WAVE;
+  // quarter of the ids owned by this wave, a multiple of the wave width
+  const int per = ((A + kPermWaves - 1) / kPermWaves + MOE_WAVE - 1) / MOE_WAVE * MOE_WAVE;
+  const int lo = min(wave * per, A), hi = min(lo + per, A);   // lo == hi: nothing to scan
 
-  const int tid = threadIdx.x;
-  const int lane = tid & (MOE_WAVE - 1);
-  const int wave = tid / MOE_WAVE;
-
-  for (int e = tid; e < E; e += kPermThreads) s_hist[e] = 0;
-  __syncthreads();
-  for (int i = tid; i < A; i += kPermThreads) {
-    const int x = topk_idx[i];
-    if (x >= 0 && x < E) atomicAdd(&s_hist[x], 1);
+  // kPermUnroll independent loads are issued before any of them is used, so a
+  // scan costs one memory round trip per 1024 ids instead of one per 64
+  int eq = 0, less = 0;
+  for (int base = lo; base < hi; base += MOE_WAVE * kPermUnroll) {
+    int x[kPermUnroll];
+#pragma unroll
+    for (int u = 0; u < kPermUnroll; ++u) {
+      const int i = base + u * MOE_WAVE + lane;
+      x[u] = topk_idx[min(i, hi - 1)];
+      if (i >= hi) x[u] = -1;
+    }
+#pragma unroll
+    for (int u = 0; u < kPermUnroll; ++u) {
+      eq += __popcll(__ballot(x[u] == e));
+      less += __popcll(__ballot(x[u] >= 0 && x[u] < e));
+    }
+  }
+  if (lane == 0) {
+    s_eq[wave] = eq;
+    s_less[wave] = less;
   }
   __syncthreads();
-  if (tid == 0) {
-    int run = 0;
-    for (int e = 0; e < E; ++e) {
-      const int c = s_hist[e];
-      s_base[e] = run;
-      offset[e] = run;
-      count[e] = c;
-      run += c;
-    }
-    offset[E] = run;
+  int start = 0, total = 0;  // bucket start; ids naming e in earlier quarters
+  for (int w = 0; w < kPermWaves; ++w) {
+    start += s_less[w];
+    if (w < wave) total += s_eq[w];
   }
-  __syncthreads();
-
-  const int tiles = (A + kPermThreads - 1) / kPermThreads;
-  for (int tile = 0; tile < tiles; ++tile) {
-    for (int j = tid; j < kPermWaves * MOE_MAX_E; j += kPermThreads) (&s_wave[0][0])[j] = 0;
-    const int i = tile * kPermThreads + tid;
-    int x = -1;
-    if (i < A) {
-      x = topk_idx[i];
-      if (x < 0 || x >= E) x = -1;
+  if (threadIdx.x == 0) {
+    const int n = s_eq[0] + s_eq[1] + s_eq[2] + s_eq[3];
+    count[e] = n;
+    offset[e] = start;
+    if (e == E - 1) offset[E] = start + n;
+  }
+  int run = start + total;
+  for (int base = lo; base < hi; base += MOE_WAVE * kPermUnroll) {
+    int x[kPermUnroll];
+#pragma unroll
+    for (int u = 0; u < kPermUnroll; ++u) {
+      const int i = base + u * MOE_WAVE + lane;
+      x[u] = topk_idx[min(i, hi - 1)];
+      if (i >= hi) x[u] = e + 1;   // padding lanes match nothing
     }
-    // rank among the lanes of this wave that carry the same expert id
-    unsigned long long todo = __ballot(x >= 0);
-    int rank = 0, group = 0;
-    bool leader = false;
-    while (todo) {
-      const int first = __ffsll((long long)todo) - 1;
-      const int lx = __shfl(x, first, MOE_WAVE);
-      const unsigned long long same = __ballot(x == lx);
-      if (x == lx) {
-        rank = __popcll(same & ((1ull << lane) - 1ull));
-        group = __popcll(same);
-        leader = (lane == first);
-      }
-      todo &= ~same;
-    }
-    __syncthreads();  // zeroing done
-    if (leader) s_wave[wave][x] = group;
-    __syncthreads();
-    for (int e = tid; e < E; e += kPermThreads) {
-      int run = s_base[e];
-      for (int w = 0; w < kPermWaves; ++w) {
-        const int c = s_wave[w][e];
-        s_wave[w][e] = run;
-        run += c;
-      }
-      s_base[e] = run;
-    }
-    __syncthreads();
-    if (i < A) {
-      if (x >= 0) {
-        const int pos = s_wave[wave][x] + rank;
+#pragma unroll
+    for (int u = 0; u < kPermUnroll; ++u) {
+      const int i = base + u * MOE_WAVE + lane;
+      const unsigned long long m = __ballot(x[u] == e);
+      if (x[u] == e) {
+        const int pos = run + __popcll(m & ((1ull << lane) - 1ull));
         perm[pos] = i;
         inv_perm[i] = pos;
-      } else {
-        inv_perm[i] = -1;
+      } else if (e == 0 && i < hi && (x[u] < 0 || x[u] >= E)) {
+        inv_perm[i] = -1;   // out-of-range index: in no bucket
       }
+      run += __popcll(m);
     }
-    __syncthreads();
   }
 }
 
@@ -103,7 +94,7 @@ __global__ __launch_bounds__(kPermThreads) void permute_kernel(
 moe_status launch_permute(const moe_shape& s, const int32_t* topk_idx, int32_t* count,
                           int32_t* offset, int32_t* perm, int32_t* inv_perm,
                           hipStream_t stream) {
-  hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(kPermThreads), 0, stream, topk_idx, count,
+  hipLaunchKernelGGL(permute_kernel, dim3(s.E), dim3(kPermThreads), 0, stream, topk_idx, count,
                      offset, perm, inv_perm, s.T * s.k, s.E);
   MOE_HIP(hipGetLastError());
   return MOE_OK;

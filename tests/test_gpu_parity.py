@@ -39,10 +39,16 @@ SMALL = [
     _small("s_bf16_ragged", T=150, E=2, k=1, H=384, F=256),       # > 64 rows per expert
     _small("s_bf16_many", T=33, E=60, k=4, H=128, F=128, S=1, bias="zipf", bias_scale=1.1),
     _small("s_bf16_e128", T=17, E=128, k=8, H=256, F=128),
+    _small("s_bf16_big_blocks", T=300, E=4, k=2, H=256, F=384, S=1),   # > 128 rows per expert
+    _small("s_bf16_odd_chunks", T=20, E=4, k=1, H=128, F=1408, bias="none"),  # 11 k-chunks of 128
     _small("s_bf16_one", T=1, E=8, k=2),
     _small("s_bf16_k_eq_e", T=9, E=3, k=3),
     _small("s_f32", dtype="f32", T=19, H=64, F=96, S=1),
     _small("s_f32_e1", dtype="f32", T=5, E=1, k=1, H=72, F=40),
+    # >= 96 tokens take the matrix-core router: ragged hidden size, E past a tile, E = 128
+    _small("s_f32_mfma_route", dtype="f32", T=130, E=5, k=2, H=72, F=40),
+    _small("s_bf16_mfma_route_e128", T=100, E=128, k=8, H=256, F=128),
+    _small("s_bf16_mfma_route_e20", T=97, E=20, k=3, H=384, F=128, S=1),
 ]
 
 
@@ -130,6 +136,33 @@ def test_permute(B):
         assert np.array_equal(d["offset"].cpu().numpy(), offset)
         assert np.array_equal(d["perm"].cpu().numpy(), perm)
         assert np.array_equal(d["inv"].cpu().numpy(), inv)
+
+
+def test_permute_drops_out_of_range_indices(B):
+    r = np.random.Generator(np.random.PCG64(12))
+    T, E, k = 300, 7, 3
+    idx = r.integers(0, E, size=(T, k)).astype(np.int32)
+    bad = r.random((T, k)) < 0.1
+    idx[bad] = np.where(r.random(bad.sum()) < 0.5, -1, E + 3)
+    sh = B.make_shape(T, 128, E, k, 128, 0, "bf16")
+    A = T * k
+    cnt = torch.empty(E, dtype=torch.int32, device="cuda")
+    off = torch.empty(E + 1, dtype=torch.int32, device="cuda")
+    perm = torch.full((A,), -7, dtype=torch.int32, device="cuda")
+    inv = torch.full((A,), -7, dtype=torch.int32, device="cuda")
+    B.moe_permute(sh, to_dev(idx), cnt, off, perm, inv)
+    torch.cuda.synchronize()
+    flat = idx.reshape(-1)
+    valid = (flat >= 0) & (flat < E)
+    ids = np.nonzero(valid)[0]
+    want = ids[np.argsort(flat[ids], kind="stable")]
+    nv = len(ids)
+    assert np.array_equal(perm.cpu().numpy()[:nv], want)
+    assert off.cpu().numpy()[-1] == nv
+    assert np.array_equal(cnt.cpu().numpy(), np.bincount(flat[valid], minlength=E))
+    invh = inv.cpu().numpy()
+    assert np.all(invh[~valid] == -1)
+    assert np.array_equal(invh[want], np.arange(nv))
 
 
 def _ffn_and_combine(B, cfg, L, mask=None):
