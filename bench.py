@@ -30,6 +30,11 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per launch of the dominant kernel from hardware counters (FETCH_SIZE and
+# WRITE_SIZE, scaled by what the same counters read for a plain copy of known size);
+# measured offline, see profiles/gate_up_c2_mixtral_b64_hbm_traffic.md.
+MEASURED_TRAFFIC_BYTES = {("c2_mixtral", 64): 1900405248}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -311,7 +316,8 @@ def main():
                                f"resident, {len(layers)} weight sets rotated",
                    "tokens": T, "active_experts": float(np.mean(used))},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, T)),
                      "kernel": "ffn_stream_kernel<gate/up>", "kernel_ms": gu_ms,
                      "algorithmic_bytes": gu_bytes},
         "phases_ms": {k: ph[k] / max(1, ph["n_layers"]) for k in

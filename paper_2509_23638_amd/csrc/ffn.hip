@@ -58,28 +58,35 @@ struct FfnArgs {
 
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
 
-template <int MODE, int NT, int TB>
+// RT = 16-row weight tiles per wave and matrix.  A wave holds NA = 2*RT weight
+// tiles: gate/up -> tile 2*rt + m is rows (wave*RT + rt)*16.. of Wg (m = 0) or
+// Wu (m = 1); down -> tile a is rows (wave*NA + a)*16.. of Wd.  RT = 1 keeps
+// many small workgroups in flight (decode, bound by HBM); RT = 2 reuses every
+// activation fragment read from LDS for four MFMAs instead of two, which is
+// what a compute-heavy batch (prefill) needs.
+template <int MODE, int NT, int TB, int RT>
 struct Streamer {
   static constexpr int kBufBytes = buf_bytes(TB);
+  static constexpr int NA = 2 * RT;
   const FfnArgs& a;
-  const uint16_t* w0;     // this lane's first element in tile 0
-  const uint16_t* w1;     // ... in tile 1
+  const uint16_t* w[NA];  // this lane's first element in each weight tile
   unsigned char* lds;
   int lane, wave;
   size_t act_off[NT];     // element offset of this lane's activation row per tile
-  bf16x8 wreg[2][kStepsPerChunk][2];
+  static constexpr int NS = RT == 1 ? 3 : 2;   // weight chunks held: c .. c+NS-1
+  bf16x8 wreg[NS][kStepsPerChunk][NA];
   uint4 xreg[NT];
-  f32x4 acc0[NT], acc1[NT];
+  f32x4 acc[NA][NT];
 
   __device__ __forceinline__ Streamer(const FfnArgs& a_) : a(a_) {}
 
   template <int SET>
   __device__ __forceinline__ void load_weights(int c) {
 #pragma unroll
-    for (int s = 0; s < kStepsPerChunk; ++s) {
-      wreg[SET][s][0] = *reinterpret_cast<const bf16x8*>(w0 + (size_t)c * kChunk + s * kKStep);
-      wreg[SET][s][1] = *reinterpret_cast<const bf16x8*>(w1 + (size_t)c * kChunk + s * kKStep);
-    }
+    for (int s = 0; s < kStepsPerChunk; ++s)
+#pragma unroll
+      for (int i = 0; i < NA; ++i)
+        wreg[SET][s][i] = *reinterpret_cast<const bf16x8*>(w[i] + (size_t)c * kChunk + s * kKStep);
   }
 
   // wave w fetches k-step w of every tile of chunk c
@@ -105,19 +112,24 @@ struct Streamer {
       for (int t = 0; t < NT; ++t) {
         const bf16x8 b = *reinterpret_cast<const bf16x8*>(
             lds + buf * kBufBytes + ((t * kStepsPerChunk + s) * MOE_WAVE + lane) * 16);
-        acc0[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[SET][s][0], b, acc0[t], 0, 0, 0);
-        acc1[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[SET][s][1], b, acc1[t], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < NA; ++i)
+          acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[SET][s][i], b, acc[i][t], 0, 0, 0);
       }
     }
   }
 
+  // Chunk c multiplies while the weights of the next NS-1 chunks are in flight.
+  // With three register sets and two waves per SIMD about 128 KB per compute
+  // unit are on their way from HBM, enough to cover the memory latency; the
+  // two-tile variant has no registers left for a third set.  The activations
+  // of chunk c+1 come from L2; their fetch is issued before the weight fetch
+  // because it is waited for first (loads complete in order).
   template <int SET>
   __device__ __forceinline__ void step(int c, int nchunks) {
     const bool more = c + 1 < nchunks;
-    if (more) {
-      load_act(c + 1);              // issued first: needed first (LDS hand-over)
-      load_weights<SET ^ 1>(c + 1);
-    }
+    if (more) load_act(c + 1);
+    if (c + NS - 1 < nchunks) load_weights<(SET + NS - 1) % NS>(c + NS - 1);
     multiply<SET>(c & 1);
     if (more) store_act((c + 1) & 1);
     __syncthreads();
@@ -126,43 +138,56 @@ struct Streamer {
   __device__ __forceinline__ void run() {
     const int nchunks = a.K / kChunk;
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      acc0[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-      acc1[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
+    for (int i = 0; i < NA; ++i)
+#pragma unroll
+      for (int t = 0; t < NT; ++t) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
     load_act(0);
     load_weights<0>(0);
+    if (NS == 3 && nchunks > 1) load_weights<1>(1);
     store_act(0);
     __syncthreads();
     int c = 0;
-    for (; c + 1 < nchunks; c += 2) {
-      step<0>(c, nchunks);
-      step<1>(c + 1, nchunks);
+    if (NS == 3) {
+      for (; c + 2 < nchunks; c += 3) {
+        step<0>(c, nchunks);
+        step<1>(c + 1, nchunks);
+        step<2 % NS>(c + 2, nchunks);
+      }
+      if (c < nchunks) step<0>(c, nchunks);
+      if (c + 1 < nchunks) step<1>(c + 1, nchunks);
+    } else {
+      for (; c + 1 < nchunks; c += 2) {
+        step<0>(c, nchunks);
+        step<1>(c + 1, nchunks);
+      }
+      if (c < nchunks) step<0>(c, nchunks);
     }
-    if (c < nchunks) step<0>(c, nchunks);
   }
 };
 
 // One workgroup: expert `e`, output rows [n0, n0 + rows per WG), bucket rows
-// [r0, min(r0 + 64, row_end)).
-template <int MODE, int NT, int TB>
+// [r0, min(r0 + 16*TB, row_end)).
+template <int MODE, int NT, int TB, int RT>
 __device__ __forceinline__ void ffn_block(const FfnArgs& a, const uint16_t* W0, const uint16_t* W1,
                                           int n0, int r0, int row_end, int shared_base,
                                           unsigned char* lds) {
-  Streamer<MODE, NT, TB> st(a);
+  constexpr int NA = 2 * RT;
+  Streamer<MODE, NT, TB, RT> st(a);
   st.lds = lds;
   st.lane = threadIdx.x & (MOE_WAVE - 1);
   st.wave = threadIdx.x / MOE_WAVE;
   const int r = st.lane & 15, g = st.lane >> 4;
-  int nrow0, nrow1;  // first output row of this wave's two tiles
-  if (MODE == kGateUp) {
-    nrow0 = nrow1 = n0 + st.wave * 16;
-  } else {
-    nrow0 = n0 + st.wave * 32;
-    nrow1 = nrow0 + 16;
+  int nrow[NA];  // first output row of each of this wave's weight tiles
+#pragma unroll
+  for (int i = 0; i < NA; ++i) {
+    if (MODE == kGateUp) {
+      nrow[i] = n0 + (st.wave * RT + (i >> 1)) * 16;
+      st.w[i] = ((i & 1) ? W1 : W0) + (size_t)(nrow[i] + r) * a.K + g * 8;
+    } else {
+      nrow[i] = n0 + (st.wave * NA + i) * 16;
+      st.w[i] = W0 + (size_t)(nrow[i] + r) * a.K + g * 8;
+    }
   }
-  st.w0 = W0 + (size_t)(nrow0 + r) * a.K + g * 8;
-  st.w1 = W1 + (size_t)(nrow1 + r) * a.K + g * 8;
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
     const int p = min(r0 + t * 16 + r, row_end - 1);  // clamp; extra columns are dropped
@@ -179,25 +204,29 @@ __device__ __forceinline__ void ffn_block(const FfnArgs& a, const uint16_t* W0, 
     const int p = r0 + t * 16 + r;
     if (p >= row_end) continue;
     if (MODE == kGateUp) {
-      uint16_t hb[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) hb[j] = f32_to_bf16_bits(silu_f(st.acc0[t][j]) * st.acc1[t][j]);
-      uint2 pk;
-      pk.x = (uint32_t)hb[0] | ((uint32_t)hb[1] << 16);
-      pk.y = (uint32_t)hb[2] | ((uint32_t)hb[3] << 16);
       uint16_t* h = static_cast<uint16_t*>(a.out);
-      *reinterpret_cast<uint2*>(h + (size_t)p * a.N + nrow0 + 4 * g) = pk;
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        uint16_t hb[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          hb[j] = f32_to_bf16_bits(silu_f(st.acc[2 * rt][t][j]) * st.acc[2 * rt + 1][t][j]);
+        uint2 pk;
+        pk.x = (uint32_t)hb[0] | ((uint32_t)hb[1] << 16);
+        pk.y = (uint32_t)hb[2] | ((uint32_t)hb[3] << 16);
+        *reinterpret_cast<uint2*>(h + (size_t)p * a.N + nrow[2 * rt] + 4 * g) = pk;
+      }
     } else {
       float* y = static_cast<float*>(a.out);
-      *reinterpret_cast<float4*>(y + (size_t)p * a.N + nrow0 + 4 * g) =
-          make_float4(st.acc0[t][0], st.acc0[t][1], st.acc0[t][2], st.acc0[t][3]);
-      *reinterpret_cast<float4*>(y + (size_t)p * a.N + nrow1 + 4 * g) =
-          make_float4(st.acc1[t][0], st.acc1[t][1], st.acc1[t][2], st.acc1[t][3]);
+#pragma unroll
+      for (int i = 0; i < NA; ++i)
+        *reinterpret_cast<float4*>(y + (size_t)p * a.N + nrow[i] + 4 * g) =
+            make_float4(st.acc[i][t][0], st.acc[i][t][1], st.acc[i][t][2], st.acc[i][t][3]);
     }
   }
 }
 
-template <int MODE, int TB>
+template <int MODE, int TB, int RT>
 __global__ __launch_bounds__(kThreads) void ffn_stream_kernel(FfnArgs a, ExpertTable tab,
                                                               GroupList groups) {
   constexpr int kTokBlock = 16 * TB;
@@ -220,25 +249,25 @@ __global__ __launch_bounds__(kThreads) void ffn_stream_kernel(FfnArgs a, ExpertT
   if (MODE == kGateUp) {
     W0 = static_cast<const uint16_t*>(tab.Wg[e]);
     W1 = static_cast<const uint16_t*>(tab.Wu[e]);
-    n0 = blockIdx.x * (kWaves * 16);
+    n0 = blockIdx.x * (kWaves * 16 * RT);
   } else {
     W0 = W1 = static_cast<const uint16_t*>(tab.Wd[e]);
-    n0 = blockIdx.x * (kWaves * 32);
+    n0 = blockIdx.x * (kWaves * 32 * RT);
   }
   // rows past the bucket's end are clamped on load and dropped on store, so a
   // larger tile count than needed is only wasted arithmetic
   if (TB <= 4) {
     switch (nt) {
-      case 1: ffn_block<MODE, 1, TB>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
-      case 2: ffn_block<MODE, 2, TB>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
-      case 3: ffn_block<MODE, 3, TB>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
-      default: ffn_block<MODE, 4, TB>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
+      case 1: ffn_block<MODE, 1, TB, RT>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
+      case 2: ffn_block<MODE, 2, TB, RT>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
+      case 3: ffn_block<MODE, 3, TB, RT>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
+      default: ffn_block<MODE, 4, TB, RT>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
     }
   } else {
-    if (nt <= 2) ffn_block<MODE, 2, TB>(a, W0, W1, n0, r0, row_end, shared_base, lds);
-    else if (nt <= 4) ffn_block<MODE, 4, TB>(a, W0, W1, n0, r0, row_end, shared_base, lds);
-    else if (nt <= 6) ffn_block<MODE, 6, TB>(a, W0, W1, n0, r0, row_end, shared_base, lds);
-    else ffn_block<MODE, TB, TB>(a, W0, W1, n0, r0, row_end, shared_base, lds);
+    if (nt <= 2) ffn_block<MODE, 2, TB, RT>(a, W0, W1, n0, r0, row_end, shared_base, lds);
+    else if (nt <= 4) ffn_block<MODE, 4, TB, RT>(a, W0, W1, n0, r0, row_end, shared_base, lds);
+    else if (nt <= 6) ffn_block<MODE, 6, TB, RT>(a, W0, W1, n0, r0, row_end, shared_base, lds);
+    else ffn_block<MODE, TB, TB, RT>(a, W0, W1, n0, r0, row_end, shared_base, lds);
   }
 }
 
@@ -442,15 +471,20 @@ bool use_splitk_down(const moe_shape& s) {
   return rows <= 24.0 && (s.S == 0 || s.T <= 32);
 }
 
-// 128-row passes once an expert is expected to see more than 48 rows (or when
-// shared experts, which see every token, have more than 64).
-// MOE_TUNE_BLOCK=4|8 overrides the choice (for measurements).
-bool use_big_blocks(const moe_shape& s) {
+// Which stream-kernel variant serves a shape:
+//   0: 64-row passes, one weight tile per wave and matrix (decode)
+//   1: 128-row passes, so an expert's weights are still read once when it is
+//      expected to see more than 48 rows
+//   2: 128-row passes and two weight tiles per wave and matrix (prefill): every
+//      activation fragment read from LDS feeds four MFMAs
+// MOE_TUNE_BLOCK=0|1|2 overrides the choice (for measurements).
+int block_variant(const moe_shape& s) {
   static const char* env = getenv("MOE_TUNE_BLOCK");
-  if (env && env[0] == '4') return false;
-  if (env && env[0] == '8') return true;
+  if (env && env[0] >= '0' && env[0] <= '2') return env[0] - '0';
   const double rows = (double)s.T * s.k / s.E;
-  return rows > 48.0 || (s.S > 0 && s.T > 64);
+  if (rows > 96.0 || (s.S > 0 && s.T > 256)) return 2;
+  if (rows > 48.0 || (s.S > 0 && s.T > 64)) return 1;
+  return 0;
 }
 
 // Phase 1 (gate and up projections, SiLU gate) for the experts in `groups`.
@@ -461,11 +495,15 @@ moe_status launch_ffn_gate_up(const moe_shape& s, const void* X, const int32_t* 
   const int A = s.T * s.k;
   if (s.dtype == MOE_BF16) {
     FfnArgs gu{static_cast<const uint16_t*>(X), perm, offset, h, s.T, s.k, s.E, A, s.H, s.F};
-    if (use_big_blocks(s)) {
-      hipLaunchKernelGGL((ffn_stream_kernel<kGateUp, 8>), dim3(s.F / (kWaves * 16), groups.n, (s.T + 127) / 128),
+    const int v = block_variant(s);
+    if (v == 2 && s.F % (kWaves * 32) == 0) {
+      hipLaunchKernelGGL((ffn_stream_kernel<kGateUp, 8, 2>), dim3(s.F / (kWaves * 32), groups.n, (s.T + 127) / 128),
+                         dim3(kThreads), 0, stream, gu, tab, groups);
+    } else if (v >= 1) {
+      hipLaunchKernelGGL((ffn_stream_kernel<kGateUp, 8, 1>), dim3(s.F / (kWaves * 16), groups.n, (s.T + 127) / 128),
                          dim3(kThreads), 0, stream, gu, tab, groups);
     } else {
-      hipLaunchKernelGGL((ffn_stream_kernel<kGateUp, 4>), dim3(s.F / (kWaves * 16), groups.n, (s.T + 63) / 64),
+      hipLaunchKernelGGL((ffn_stream_kernel<kGateUp, 4, 1>), dim3(s.F / (kWaves * 16), groups.n, (s.T + 63) / 64),
                          dim3(kThreads), 0, stream, gu, tab, groups);
     }
   } else {
@@ -491,11 +529,14 @@ moe_status launch_ffn_down(const moe_shape& s, const void* h, const int32_t* per
       const int tok_blocks = (s.T + kSplitTok - 1) / kSplitTok;
       hipLaunchKernelGGL(ffn_down_splitk_kernel, dim3(s.H / kSplitRows, groups.n, tok_blocks),
                          dim3(kThreads), 0, stream, dn, tab, groups);
-    } else if (use_big_blocks(s)) {
-      hipLaunchKernelGGL((ffn_stream_kernel<kDown, 8>), dim3(s.H / (kWaves * 32), groups.n, (s.T + 127) / 128),
+    } else if (block_variant(s) == 2 && s.H % (kWaves * 64) == 0) {
+      hipLaunchKernelGGL((ffn_stream_kernel<kDown, 8, 2>), dim3(s.H / (kWaves * 64), groups.n, (s.T + 127) / 128),
+                         dim3(kThreads), 0, stream, dn, tab, groups);
+    } else if (block_variant(s) >= 1) {
+      hipLaunchKernelGGL((ffn_stream_kernel<kDown, 8, 1>), dim3(s.H / (kWaves * 32), groups.n, (s.T + 127) / 128),
                          dim3(kThreads), 0, stream, dn, tab, groups);
     } else {
-      hipLaunchKernelGGL((ffn_stream_kernel<kDown, 4>), dim3(s.H / (kWaves * 32), groups.n, (s.T + 63) / 64),
+      hipLaunchKernelGGL((ffn_stream_kernel<kDown, 4, 1>), dim3(s.H / (kWaves * 32), groups.n, (s.T + 63) / 64),
                          dim3(kThreads), 0, stream, dn, tab, groups);
     }
   } else {
