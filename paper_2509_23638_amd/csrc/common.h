@@ -38,7 +38,7 @@ static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 
 // Workspace carve-up (all offsets 256-byte aligned).
 struct WorkspaceLayout {
-  size_t topk_idx, topk_w, count, offset, perm, inv_perm, h, y, total;
+  size_t topk_idx, topk_w, count, offset, perm, inv_perm, plan, h, y, total;
 };
 WorkspaceLayout workspace_layout(const moe_shape& s);
 
@@ -58,6 +58,14 @@ struct GroupList {
   uint8_t id[MOE_MAX_GROUPS];
 };
 
+// Scratch of the grouped FFN inside a workspace: the intermediate h and the
+// row-block plan of the tiled (prefill) kernels.
+struct FfnScratch {
+  void* h;
+  int32_t* plan;
+};
+size_t plan_bytes(const moe_shape& s);
+
 // internal launchers (each enqueues on `stream`, returns a status)
 moe_status launch_route(const moe_shape& s, const void* X, const void* Wr, const float* bias,
                         int32_t* topk_idx, float* topk_w, double* logits_out, hipStream_t stream);
@@ -65,17 +73,17 @@ moe_status launch_permute(const moe_shape& s, const int32_t* topk_idx, int32_t* 
                           int32_t* offset, int32_t* perm, int32_t* inv_perm, hipStream_t stream);
 moe_status launch_grouped_ffn(const moe_shape& s, const void* X, const int32_t* perm,
                               const int32_t* offset, const ExpertTable& tab, const GroupList& groups,
-                              float* Y, void* h, hipStream_t stream);
+                              float* Y, const FfnScratch& scratch, hipStream_t stream);
 moe_status launch_ffn_gate_up(const moe_shape& s, const void* X, const int32_t* perm,
                               const int32_t* offset, const ExpertTable& tab,
-                              const GroupList& groups, void* h, hipStream_t stream);
-moe_status launch_ffn_down(const moe_shape& s, const void* h, const int32_t* perm,
+                              const GroupList& groups, const FfnScratch& scratch, hipStream_t stream);
+moe_status launch_ffn_down(const moe_shape& s, const FfnScratch& scratch, const int32_t* perm,
                            const int32_t* offset, const ExpertTable& tab, const GroupList& groups,
                            float* Y, hipStream_t stream);
 moe_status launch_ffn_gated(const moe_shape& s, const void* X, const int32_t* perm,
                             const int32_t* offset, const ExpertTable& tab, const GroupList& groups,
-                            float* Y, void* h, hipStream_t stream, hipEvent_t wait_gu,
-                            hipEvent_t wait_d, hipEvent_t mid);
+                            float* Y, const FfnScratch& scratch, hipStream_t stream,
+                            hipEvent_t wait_gu, hipEvent_t wait_d, hipEvent_t mid);
 moe_status launch_combine(const moe_shape& s, const float* Y, const float* topk_w,
                           const int32_t* inv_perm, const void* residual, void* out,
                           hipStream_t stream);

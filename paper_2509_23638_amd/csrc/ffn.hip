@@ -271,6 +271,296 @@ __global__ __launch_bounds__(kThreads) void ffn_stream_kernel(FfnArgs a, ExpertT
   }
 }
 
+// ------------------------------------------------ prefill: tiled kernel ----
+// Many rows per expert: the FFN is a grouped GEMM and the bound moves from the
+// weight stream to the matrix cores and to the bytes that reach a compute unit
+// per flop.  One workgroup (four waves as 2 x 2) owns 256 bucket rows x 128
+// weight rows (64 gate + 64 up rows, or 128 down rows); a wave keeps 8 x 4 MFMA
+// tiles of accumulators.  Both operands go global -> LDS with the
+// direct-to-LDS form of the global load (no staging registers), three 64-wide
+// k-stages of 48 KiB in a ring, two of them in flight while one multiplies.
+//
+// Fetch shape.  Measured on this chip, a wave-wide 16-byte load whose lanes
+// cover 16 rows x 64 B runs at a third of the rate of one that covers 8 rows x
+// 128 B (whole cache lines), even out of L2.  So one fetch instruction takes 8
+// rows x 64 k, and a 16-row x 64-k operand block is two of them (2 KiB).  The
+// hardware stores lane l at base + 16 l; which 16-byte chunk of its row a lane
+// fetches is ours to choose, so the chunks are XOR-swizzled: lane (row8 = l/8,
+// slot = l%8) of half u fetches chunk slot ^ sw, sw = row8 for the upper half
+// and (row8 + 1) % 8 for the lower.  The MFMA operand read -- lane (r, g) wants
+// row r, chunk 4 s + g of k-step s -- then spreads its sixteen rows over all
+// LDS banks instead of piling them on eight.
+//
+// The waves take the token tiles alternately so that a partly filled 256-row
+// block is still shared evenly; tiles past the bucket's end are fetched
+// (clamped rows) but not multiplied.  Work items are dealt so that each XCD
+// (own L2) gets a contiguous run of them.
+#ifdef MOE_TILE_TIMING
+__device__ unsigned long long g_tile_ts[8];
+#define TILE_T() clock64()
+#else
+#define TILE_T() 0ull
+#endif
+constexpr int kTileRows = 256;                    // bucket rows per workgroup
+constexpr int kTileK = 64;                        // contraction depth of a stage
+constexpr int kDblFrag = 2 * kFragBytes;          // 16 rows x 64 k
+constexpr int kTileStage = 24 * kDblFrag;         // 16 token + 8 weight blocks = 48 KiB
+constexpr int kTileStages = 3;
+constexpr int kTileLds = kTileStage * kTileStages;
+constexpr int kFetchPerWave = 12;                 // 48 fetches per stage over 4 waves
+
+// plan[0] = number of row blocks; then (group index, first row, end row) per block
+__global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict__ offset, int T,
+                                                       int E, int A, GroupList groups,
+                                                       int32_t* __restrict__ plan) {
+  __shared__ int s_begin[MOE_MAX_GROUPS], s_rows[MOE_MAX_GROUPS], s_first[MOE_MAX_GROUPS + 1];
+  const int i = threadIdx.x;
+  if (i < groups.n) {
+    const int e = groups.id[i];
+    int b, n;
+    if (e < E) {
+      b = offset[e];
+      n = offset[e + 1] - b;
+    } else {
+      b = A + (e - E) * T;
+      n = T;
+    }
+    s_begin[i] = b;
+    s_rows[i] = n;
+  }
+  __syncthreads();
+  if (i == 0) {
+    int run = 0;
+    for (int q = 0; q < groups.n; ++q) {
+      s_first[q] = run;
+      run += (s_rows[q] + kTileRows - 1) / kTileRows;
+    }
+    s_first[groups.n] = run;
+    plan[0] = run;
+  }
+  __syncthreads();
+  if (i < groups.n) {
+    const int nb = s_first[i + 1] - s_first[i];
+    for (int q = 0; q < nb; ++q) {
+      int32_t* p = plan + 1 + 3 * (s_first[i] + q);
+      p[0] = i;
+      p[1] = s_begin[i] + q * kTileRows;
+      p[2] = s_begin[i] + s_rows[i];
+    }
+  }
+}
+
+// NJ = token tiles per wave that are multiplied (the block's tiles, taken
+// alternately by the two wave rows, rounded up): a compile-time bound, so the
+// accumulators stay in registers and a short block costs what it uses.
+template <int MODE, int NJ>
+__device__ __forceinline__ void ffn_tile_block(const FfnArgs& a, const ExpertTable& tab, int e,
+                                               int r0, int row_end, int slab,
+                                               unsigned char* ring) {
+  const int shared_base = e >= a.E ? a.A + (e - a.E) * a.T : -1;
+  const int lane = threadIdx.x & (MOE_WAVE - 1), wave = threadIdx.x / MOE_WAVE;
+  const int wm = wave & 1, wn = wave >> 1;
+  const int n0 = slab * (MODE == kGateUp ? 64 : 128);
+
+  // Blocks of a stage: 0..15 = token tiles, 16..23 = weight tiles (gate/up:
+  // 16..19 gate rows n0.., 20..23 the same rows of up).  Every block is two
+  // fetches (rows 0..7 and 8..15); wave w issues the fetches h = w + 4 q.
+  const uint16_t* src[kFetchPerWave];
+  {
+    const int row8 = lane >> 3, slot = lane & 7;
+#pragma unroll
+    for (int q = 0; q < kFetchPerWave; ++q) {
+      const int h = wave + 4 * q, blk = h >> 1, u = h & 1;
+      const int chunk = slot ^ (u ? ((row8 + 1) & 7) : row8);
+      const int rr = 8 * u + row8;   // row inside the 16-row block
+      const uint16_t* rowp;
+      if (blk < 16) {
+        const int p = min(r0 + blk * 16 + rr, row_end - 1);
+        int row;
+        if (MODE == kGateUp) row = shared_base >= 0 ? p - shared_base : a.perm[p] / a.k;
+        else row = p;
+        rowp = a.act + (size_t)row * a.K;
+      } else {
+        const int j = blk - 16;
+        if (MODE == kGateUp) {
+          const uint16_t* W = static_cast<const uint16_t*>(j < 4 ? tab.Wg[e] : tab.Wu[e]);
+          rowp = W + (size_t)(n0 + (j & 3) * 16 + rr) * a.K;
+        } else {
+          rowp = static_cast<const uint16_t*>(tab.Wd[e]) + (size_t)(n0 + j * 16 + rr) * a.K;
+        }
+      }
+      src[q] = rowp + chunk * 8;
+    }
+  }
+  auto fetch = [&](int st) {
+    unsigned char* base = ring + (st % kTileStages) * kTileStage;
+#pragma unroll
+    for (int q = 0; q < kFetchPerWave; ++q)
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(src[q] + (size_t)st * kTileK),
+          (__attribute__((address_space(3))) void*)(base + (wave + 4 * q) * kFragBytes), 16, 0, 0);
+  };
+  // where lane (r, g) finds row r, chunk 4 s + g of a block, for k-step s = 0, 1
+  int rd[2];
+  {
+    const int r = lane & 15, g = lane >> 4;
+    const int u = r >> 3, row8 = r & 7, sw = u ? ((row8 + 1) & 7) : row8;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) rd[ks] = u * kFragBytes + (row8 * 8 + ((4 * ks + g) ^ sw)) * 16;
+  }
+
+  f32x4 acc[4][NJ];   // this wave's token tiles are wm, wm + 2, ...
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int ns = a.K / kTileK;
+#ifdef MOE_TILE_TIMING
+  unsigned long long t_wait = 0, t_bar = 0, t_mma = 0, t_all = TILE_T();
+#endif
+  fetch(0);
+  if (ns > 1) fetch(1);
+  for (int st = 0; st < ns; ++st) {
+#ifdef MOE_TILE_TIMING
+    const unsigned long long t0 = TILE_T();
+#endif
+    // this wave's fetches of stage st have landed once at most the fetches of
+    // the one younger stage already issued are still outstanding
+    if (st + 1 < ns) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#ifdef MOE_TILE_TIMING
+    const unsigned long long t1 = TILE_T();
+#endif
+    __syncthreads();   // everybody's fetches of stage st landed; stage st-1 has been consumed
+#ifdef MOE_TILE_TIMING
+    const unsigned long long t2 = TILE_T();
+#endif
+    if (st + 2 < ns) fetch(st + 2);   // into the buffer stage st-1 used
+    const unsigned char* base = ring + (st % kTileStages) * kTileStage;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      // all LDS reads of the k-step are issued before its first MFMA
+      bf16x8 wf[4], tf[NJ];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        int blk;
+        if (MODE == kGateUp) blk = 16 + (i >> 1) * 4 + wn * 2 + (i & 1);
+        else blk = 16 + wn * 4 + i;
+        wf[i] = *reinterpret_cast<const bf16x8*>(base + blk * kDblFrag + rd[ks]);
+      }
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+        tf[j] = *reinterpret_cast<const bf16x8*>(base + (wm + 2 * j) * kDblFrag + rd[ks]);
+      __builtin_amdgcn_sched_barrier(0);   // keep the scheduler from sinking the reads again
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[i], tf[j], acc[i][j], 0, 0, 0);
+    }
+#ifdef MOE_TILE_TIMING
+    asm volatile("s_nop 0" ::: "memory");
+    const unsigned long long t3 = TILE_T();
+    t_wait += t1 - t0; t_bar += t2 - t1; t_mma += t3 - t2;
+#endif
+  }
+#ifdef MOE_TILE_TIMING
+  if (blockIdx.x == 64 && (threadIdx.x & 63) == 0) {
+    const int w_ = threadIdx.x >> 6;
+    if (w_ == 0) { g_tile_ts[0] = t_wait; g_tile_ts[1] = t_bar; g_tile_ts[2] = t_mma; g_tile_ts[3] = TILE_T() - t_all; g_tile_ts[4] = ns; g_tile_ts[5] = NJ; }
+    if (w_ == 3) { g_tile_ts[6] = t_wait; g_tile_ts[7] = t_bar; }
+  }
+#endif
+
+  // D layout: lane holds rows 4*g .. 4*g+3 of the 16-row weight tile, column r = token
+  const int r = lane & 15, g = lane >> 4;
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int p = r0 + (wm + 2 * j) * 16 + r;
+    if (p >= row_end) continue;
+    if (MODE == kGateUp) {
+      uint16_t* h = static_cast<uint16_t*>(a.out);
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        uint16_t hb[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) hb[q] = f32_to_bf16_bits(silu_f(acc[i][j][q]) * acc[2 + i][j][q]);
+        uint2 pk;
+        pk.x = (uint32_t)hb[0] | ((uint32_t)hb[1] << 16);
+        pk.y = (uint32_t)hb[2] | ((uint32_t)hb[3] << 16);
+        *reinterpret_cast<uint2*>(h + (size_t)p * a.N + n0 + (wn * 2 + i) * 16 + 4 * g) = pk;
+      }
+    } else {
+      float* y = static_cast<float*>(a.out);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        *reinterpret_cast<float4*>(y + (size_t)p * a.N + n0 + (wn * 4 + i) * 16 + 4 * g) =
+            make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+    }
+  }
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kThreads, 1) void ffn_tile_kernel(FfnArgs a, ExpertTable tab,
+                                                               GroupList groups,
+                                                               const int32_t* __restrict__ plan) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char ring[];
+  // Work items = (row block, weight slab), slab fastest.  Workgroups are dealt
+  // to the 8 XCDs round-robin by their linear id, and every XCD has its own
+  // L2: give each XCD one contiguous eighth of the items, so that the slabs
+  // that share a row block's activations (and the row blocks that share a
+  // shared expert's weights) run next to each other behind the same L2.
+  const int slabs = a.N / (MODE == kGateUp ? 64 : 128);
+  const int total = plan[0] * slabs;
+  const int per_xcd = (total + 7) / 8;
+  const int local = blockIdx.x >> 3;
+  const int item = (blockIdx.x & 7) * per_xcd + local;
+  if (local >= per_xcd || item >= total) return;
+  const int blk = item / slabs, slab = item - blk * slabs;
+  const int e = groups.id[plan[1 + 3 * blk]];
+  const int r0 = plan[2 + 3 * blk], row_end = plan[3 + 3 * blk];
+  const int tiles = (min(row_end - r0, kTileRows) + 15) / 16;
+  if (tiles <= 4) ffn_tile_block<MODE, 2>(a, tab, e, r0, row_end, slab, ring);
+  else if (tiles <= 8) ffn_tile_block<MODE, 4>(a, tab, e, r0, row_end, slab, ring);
+  else if (tiles <= 12) ffn_tile_block<MODE, 6>(a, tab, e, r0, row_end, slab, ring);
+  else ffn_tile_block<MODE, 8>(a, tab, e, r0, row_end, slab, ring);
+}
+
+#ifdef MOE_TILE_TIMING
+}  // namespace
+}  // namespace moe
+extern "C" int moe_debug_tile_ts(unsigned long long* out8) {
+  return (int)hipMemcpyFromSymbol(out8, HIP_SYMBOL(moe::g_tile_ts), 64);
+}
+namespace moe {
+namespace {
+#endif
+
+// Upper bound on the number of 256-row blocks a launch can need.
+int max_row_blocks(const moe_shape& s) {
+  return (s.T * s.k + s.S * s.T) / kTileRows + s.E + s.S + 1;
+}
+
+template <int MODE>
+moe_status launch_tile(const moe_shape& s, const FfnArgs& args, const ExpertTable& tab,
+                       const GroupList& groups, int32_t* plan, hipStream_t stream) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    MOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_tile_kernel<MODE>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kTileLds));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, stream, args.offset, s.T, s.E, args.A,
+                     groups, plan);
+  const int slabs = MODE == kGateUp ? s.F / 64 : s.H / 128;
+  const int grid = (slabs * max_row_blocks(s) + 7) / 8 * 8;
+  hipLaunchKernelGGL((ffn_tile_kernel<MODE>), dim3(grid), dim3(kThreads), kTileLds, stream, args,
+                     tab, groups, plan);
+  MOE_HIP(hipGetLastError());
+  return MOE_OK;
+}
+
 // ------------------------------------------------------- down, split-K ----
 // Down projection for few rows per expert (decode): the four wavefronts of a
 // workgroup share the same 32 weight rows and each walks a quarter of the
@@ -475,28 +765,37 @@ bool use_splitk_down(const moe_shape& s) {
 //   0: 64-row passes, one weight tile per wave and matrix (decode)
 //   1: 128-row passes, so an expert's weights are still read once when it is
 //      expected to see more than 48 rows
-//   2: 128-row passes and two weight tiles per wave and matrix (prefill): every
+//   2: 128-row passes and two weight tiles per wave and matrix: every
 //      activation fragment read from LDS feeds four MFMAs
-// MOE_TUNE_BLOCK=0|1|2 overrides the choice (for measurements).
+//   3: the tiled kernel (256 x 256 blocks, both operands through LDS) once the
+//      batch is compute-heavy (prefill)
+// MOE_TUNE_BLOCK=0..3 overrides the choice (for measurements).
 int block_variant(const moe_shape& s) {
   static const char* env = getenv("MOE_TUNE_BLOCK");
-  if (env && env[0] >= '0' && env[0] <= '2') return env[0] - '0';
+  if (env && env[0] >= '0' && env[0] <= '3') return env[0] - '0';
   const double rows = (double)s.T * s.k / s.E;
-  if (rows > 96.0 || (s.S > 0 && s.T > 256)) return 2;
-  if (rows > 48.0 || (s.S > 0 && s.T > 64)) return 1;
+  if (rows > 96.0 || (s.S > 0 && s.T > 256)) return 3;
+  if (rows > 48.0 || (s.S > 0 && s.T > 128)) return 1;
   return 0;
 }
+
+// The tiled kernel walks the contraction in steps of 64 and owns 64 / 128 rows.
+bool tile_kernel_fits(const moe_shape& s) { return s.H % 128 == 0 && s.F % 64 == 0; }
 
 // Phase 1 (gate and up projections, SiLU gate) for the experts in `groups`.
 moe_status launch_ffn_gate_up(const moe_shape& s, const void* X, const int32_t* perm,
                               const int32_t* offset, const ExpertTable& tab,
-                              const GroupList& groups, void* h, hipStream_t stream) {
+                              const GroupList& groups, const FfnScratch& scratch,
+                              hipStream_t stream) {
   if (groups.n == 0 || s.T == 0) return MOE_OK;
   const int A = s.T * s.k;
+  void* h = scratch.h;
   if (s.dtype == MOE_BF16) {
     FfnArgs gu{static_cast<const uint16_t*>(X), perm, offset, h, s.T, s.k, s.E, A, s.H, s.F};
     const int v = block_variant(s);
-    if (v == 2 && s.F % (kWaves * 32) == 0) {
+    if (v == 3 && tile_kernel_fits(s)) {
+      return launch_tile<kGateUp>(s, gu, tab, groups, scratch.plan, stream);
+    } else if (v >= 2 && s.F % (kWaves * 32) == 0) {
       hipLaunchKernelGGL((ffn_stream_kernel<kGateUp, 8, 2>), dim3(s.F / (kWaves * 32), groups.n, (s.T + 127) / 128),
                          dim3(kThreads), 0, stream, gu, tab, groups);
     } else if (v >= 1) {
@@ -518,18 +817,21 @@ moe_status launch_ffn_gate_up(const moe_shape& s, const void* X, const int32_t* 
 }
 
 // Phase 2 (down projection) for the experts in `groups`.
-moe_status launch_ffn_down(const moe_shape& s, const void* h, const int32_t* perm,
+moe_status launch_ffn_down(const moe_shape& s, const FfnScratch& scratch, const int32_t* perm,
                            const int32_t* offset, const ExpertTable& tab, const GroupList& groups,
                            float* Y, hipStream_t stream) {
   if (groups.n == 0 || s.T == 0) return MOE_OK;
   const int A = s.T * s.k;
+  const void* h = scratch.h;
   if (s.dtype == MOE_BF16) {
     FfnArgs dn{static_cast<const uint16_t*>(h), perm, offset, Y, s.T, s.k, s.E, A, s.F, s.H};
-    if (use_splitk_down(s)) {
+    if (block_variant(s) == 3 && tile_kernel_fits(s)) {
+      return launch_tile<kDown>(s, dn, tab, groups, scratch.plan, stream);
+    } else if (use_splitk_down(s)) {
       const int tok_blocks = (s.T + kSplitTok - 1) / kSplitTok;
       hipLaunchKernelGGL(ffn_down_splitk_kernel, dim3(s.H / kSplitRows, groups.n, tok_blocks),
                          dim3(kThreads), 0, stream, dn, tab, groups);
-    } else if (block_variant(s) == 2 && s.H % (kWaves * 64) == 0) {
+    } else if (block_variant(s) >= 2 && s.H % (kWaves * 64) == 0) {
       hipLaunchKernelGGL((ffn_stream_kernel<kDown, 8, 2>), dim3(s.H / (kWaves * 64), groups.n, (s.T + 127) / 128),
                          dim3(kThreads), 0, stream, dn, tab, groups);
     } else if (block_variant(s) >= 1) {
@@ -555,20 +857,22 @@ moe_status launch_ffn_down(const moe_shape& s, const void* h, const int32_t* per
 // (may be NULL) is recorded between the phases.
 moe_status launch_ffn_gated(const moe_shape& s, const void* X, const int32_t* perm,
                             const int32_t* offset, const ExpertTable& tab, const GroupList& groups,
-                            float* Y, void* h, hipStream_t stream, hipEvent_t wait_gu,
-                            hipEvent_t wait_d, hipEvent_t mid) {
+                            float* Y, const FfnScratch& scratch, hipStream_t stream,
+                            hipEvent_t wait_gu, hipEvent_t wait_d, hipEvent_t mid) {
   if (wait_gu) MOE_HIP(hipStreamWaitEvent(stream, wait_gu, 0));
-  moe_status st = launch_ffn_gate_up(s, X, perm, offset, tab, groups, h, stream);
+  moe_status st = launch_ffn_gate_up(s, X, perm, offset, tab, groups, scratch, stream);
   if (st != MOE_OK) return st;
   if (mid) MOE_HIP(hipEventRecord(mid, stream));
   if (wait_d) MOE_HIP(hipStreamWaitEvent(stream, wait_d, 0));
-  return launch_ffn_down(s, h, perm, offset, tab, groups, Y, stream);
+  return launch_ffn_down(s, scratch, perm, offset, tab, groups, Y, stream);
 }
 
 moe_status launch_grouped_ffn(const moe_shape& s, const void* X, const int32_t* perm,
                               const int32_t* offset, const ExpertTable& tab,
-                              const GroupList& groups, float* Y, void* h, hipStream_t stream) {
-  return launch_ffn_gated(s, X, perm, offset, tab, groups, Y, h, stream, nullptr, nullptr, nullptr);
+                              const GroupList& groups, float* Y, const FfnScratch& scratch,
+                              hipStream_t stream) {
+  return launch_ffn_gated(s, X, perm, offset, tab, groups, Y, scratch, stream, nullptr, nullptr,
+                          nullptr);
 }
 
 }  // namespace moe
@@ -598,7 +902,8 @@ extern "C" moe_status moe_grouped_ffn(const moe_shape* shape, const void* X, con
     }
   }
   const moe::WorkspaceLayout L = moe::workspace_layout(*shape);
-  return moe::launch_grouped_ffn(*shape, X, perm, offset, tab, groups, Y,
-                                 static_cast<char*>(workspace) + L.h,
+  const moe::FfnScratch scratch{static_cast<char*>(workspace) + L.h,
+                                reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + L.plan)};
+  return moe::launch_grouped_ffn(*shape, X, perm, offset, tab, groups, Y, scratch,
                                  static_cast<hipStream_t>(stream));
 }
