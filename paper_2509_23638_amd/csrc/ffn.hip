@@ -44,7 +44,7 @@ constexpr int kFragBytes = MOE_WAVE * 16;        // one B fragment in LDS
 // still read once.  One LDS buffer holds TB * 4 fragments.
 constexpr int buf_bytes(int tb) { return tb * kStepsPerChunk * kFragBytes; }
 
-enum { kGateUp = 0, kDown = 1 };
+enum { kGateUp = 0, kDown = 1, kDownHalves = 2 };
 
 struct FfnArgs {
   const uint16_t* act;    // gate/up: X [T,H]; down: h [rows,F]
@@ -64,18 +64,27 @@ __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)
 // many small workgroups in flight (decode, bound by HBM); RT = 2 reuses every
 // activation fragment read from LDS for four MFMAs instead of two, which is
 // what a compute-heavy batch (prefill) needs.
+//
+// kDownHalves: the wave's two tiles are the SAME 16 rows of Wd over the first
+// and the second half of the contraction, summed at the end.  A workgroup then
+// owns 64 rows instead of 128, so a Mixtral-shaped down projection has twice
+// the workgroups (two per compute unit, like gate/up) and twice the weight
+// bytes in flight.  The halves need different activations: LDS holds both.
 template <int MODE, int NT, int TB, int RT>
 struct Streamer {
-  static constexpr int kBufBytes = buf_bytes(TB);
+  static constexpr bool kHalves = MODE == kDownHalves;
+  static constexpr int NH = kHalves ? 2 : 1;          // activation positions staged per chunk
+  static constexpr int kBufBytes = NH * buf_bytes(TB);
   static constexpr int NA = 2 * RT;
+  int half_chunks = 0;    // kDownHalves: chunks per half of the contraction
   const FfnArgs& a;
   const uint16_t* w[NA];  // this lane's first element in each weight tile
   unsigned char* lds;
   int lane, wave;
   size_t act_off[NT];     // element offset of this lane's activation row per tile
-  static constexpr int NS = RT == 1 ? 3 : 2;   // weight chunks held: c .. c+NS-1
+  static constexpr int NS = (RT == 1 && !kHalves) ? 3 : 2;   // weight chunks held: c .. c+NS-1
   bf16x8 wreg[NS][kStepsPerChunk][NA];
-  uint4 xreg[NT];
+  uint4 xreg[NH * NT];
   f32x4 acc[NA][NT];
 
   __device__ __forceinline__ Streamer(const FfnArgs& a_) : a(a_) {}
@@ -92,16 +101,19 @@ struct Streamer {
   // wave w fetches k-step w of every tile of chunk c
   __device__ __forceinline__ void load_act(int c) {
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
-      xreg[t] = *reinterpret_cast<const uint4*>(a.act + act_off[t] + (size_t)c * kChunk +
-                                                wave * kKStep + (lane >> 4) * 8);
+    for (int hf = 0; hf < NH; ++hf)
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+        xreg[hf * NT + t] = *reinterpret_cast<const uint4*>(
+            a.act + act_off[t] + (size_t)(c + hf * half_chunks) * kChunk + wave * kKStep +
+            (lane >> 4) * 8);
   }
 
   __device__ __forceinline__ void store_act(int buf) {
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
+    for (int q = 0; q < NH * NT; ++q)
       *reinterpret_cast<uint4*>(lds + buf * kBufBytes +
-                                ((t * kStepsPerChunk + wave) * MOE_WAVE + lane) * 16) = xreg[t];
+                                ((q * kStepsPerChunk + wave) * MOE_WAVE + lane) * 16) = xreg[q];
   }
 
   template <int SET>
@@ -110,11 +122,20 @@ struct Streamer {
     for (int s = 0; s < kStepsPerChunk; ++s) {
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
-        const bf16x8 b = *reinterpret_cast<const bf16x8*>(
-            lds + buf * kBufBytes + ((t * kStepsPerChunk + s) * MOE_WAVE + lane) * 16);
+        if (kHalves) {
 #pragma unroll
-        for (int i = 0; i < NA; ++i)
-          acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[SET][s][i], b, acc[i][t], 0, 0, 0);
+          for (int i = 0; i < NA; ++i) {
+            const bf16x8 b = *reinterpret_cast<const bf16x8*>(
+                lds + buf * kBufBytes + (((i * NT + t) * kStepsPerChunk + s) * MOE_WAVE + lane) * 16);
+            acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[SET][s][i], b, acc[i][t], 0, 0, 0);
+          }
+        } else {
+          const bf16x8 b = *reinterpret_cast<const bf16x8*>(
+              lds + buf * kBufBytes + ((t * kStepsPerChunk + s) * MOE_WAVE + lane) * 16);
+#pragma unroll
+          for (int i = 0; i < NA; ++i)
+            acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[SET][s][i], b, acc[i][t], 0, 0, 0);
+        }
       }
     }
   }
@@ -136,7 +157,7 @@ struct Streamer {
   }
 
   __device__ __forceinline__ void run() {
-    const int nchunks = a.K / kChunk;
+    const int nchunks = kHalves ? half_chunks : a.K / kChunk;
 #pragma unroll
     for (int i = 0; i < NA; ++i)
 #pragma unroll
@@ -183,6 +204,10 @@ __device__ __forceinline__ void ffn_block(const FfnArgs& a, const uint16_t* W0, 
     if (MODE == kGateUp) {
       nrow[i] = n0 + (st.wave * RT + (i >> 1)) * 16;
       st.w[i] = ((i & 1) ? W1 : W0) + (size_t)(nrow[i] + r) * a.K + g * 8;
+    } else if (MODE == kDownHalves) {
+      st.half_chunks = a.K / kChunk / 2;
+      nrow[i] = n0 + st.wave * 16;
+      st.w[i] = W0 + (size_t)(nrow[i] + r) * a.K + g * 8 + (size_t)i * st.half_chunks * kChunk;
     } else {
       nrow[i] = n0 + (st.wave * NA + i) * 16;
       st.w[i] = W0 + (size_t)(nrow[i] + r) * a.K + g * 8;
@@ -216,6 +241,11 @@ __device__ __forceinline__ void ffn_block(const FfnArgs& a, const uint16_t* W0, 
         pk.y = (uint32_t)hb[2] | ((uint32_t)hb[3] << 16);
         *reinterpret_cast<uint2*>(h + (size_t)p * a.N + nrow[2 * rt] + 4 * g) = pk;
       }
+    } else if (MODE == kDownHalves) {
+      float* y = static_cast<float*>(a.out);
+      *reinterpret_cast<float4*>(y + (size_t)p * a.N + nrow[0] + 4 * g) =
+          make_float4(st.acc[0][t][0] + st.acc[1][t][0], st.acc[0][t][1] + st.acc[1][t][1],
+                      st.acc[0][t][2] + st.acc[1][t][2], st.acc[0][t][3] + st.acc[1][t][3]);
     } else {
       float* y = static_cast<float*>(a.out);
 #pragma unroll
@@ -230,7 +260,7 @@ template <int MODE, int TB, int RT>
 __global__ __launch_bounds__(kThreads) void ffn_stream_kernel(FfnArgs a, ExpertTable tab,
                                                               GroupList groups) {
   constexpr int kTokBlock = 16 * TB;
-  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * buf_bytes(TB)];
+  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * (MODE == kDownHalves ? 2 : 1) * buf_bytes(TB)];
   const int e = groups.id[blockIdx.y];
   int row_begin, row_end, shared_base = -1;
   if (e < a.E) {
@@ -250,6 +280,9 @@ __global__ __launch_bounds__(kThreads) void ffn_stream_kernel(FfnArgs a, ExpertT
     W0 = static_cast<const uint16_t*>(tab.Wg[e]);
     W1 = static_cast<const uint16_t*>(tab.Wu[e]);
     n0 = blockIdx.x * (kWaves * 16 * RT);
+  } else if (MODE == kDownHalves) {
+    W0 = W1 = static_cast<const uint16_t*>(tab.Wd[e]);
+    n0 = blockIdx.x * (kWaves * 16);
   } else {
     W0 = W1 = static_cast<const uint16_t*>(tab.Wd[e]);
     n0 = blockIdx.x * (kWaves * 32 * RT);
@@ -750,15 +783,24 @@ __global__ __launch_bounds__(kThreads) void ffn_f32_kernel(F32Args a, ExpertTabl
 
 }  // namespace
 
-// The split-K down kernel pays off while an expert's bucket fits one 32-row
-// pass: expected rows per routed expert T*k/E (shared experts see T rows).
-// MOE_TUNE_DOWN=lds|splitk overrides the choice (for measurements).
-bool use_splitk_down(const moe_shape& s) {
+// Down projection at decode sizes (block variant 0):
+//   0: the stream kernel, 128 rows per workgroup
+//   1: the four-wave split-K kernel (32 rows per workgroup, activations straight
+//      from L2): best when very few experts are active, it keeps the chip full
+//   2: the stream kernel with the contraction halved inside each wave (64 rows
+//      per workgroup)
+// MOE_TUNE_DOWN=lds|splitk|halves overrides the choice (for measurements).
+int block_variant(const moe_shape& s);
+int down_variant(const moe_shape& s) {
   static const char* env = getenv("MOE_TUNE_DOWN");
-  if (env && env[0] == 'l') return false;
-  if (env && env[0] == 's') return true;
+  const bool halves_ok = (s.F / kChunk) % 2 == 0;
+  if (env && env[0] == 'l') return 0;
+  if (env && env[0] == 's') return 1;
+  if (env && env[0] == 'h' && halves_ok) return 2;
+  if (block_variant(s) != 0) return 0;
   const double rows = (double)s.T * s.k / s.E;
-  return rows <= 24.0 && (s.S == 0 || s.T <= 32);
+  if (rows <= 24.0 && (s.S == 0 || s.T <= 32)) return (rows <= 4.0 || !halves_ok) ? 1 : 2;
+  return 0;
 }
 
 // Which stream-kernel variant serves a shape:
@@ -827,7 +869,10 @@ moe_status launch_ffn_down(const moe_shape& s, const FfnScratch& scratch, const 
     FfnArgs dn{static_cast<const uint16_t*>(h), perm, offset, Y, s.T, s.k, s.E, A, s.F, s.H};
     if (block_variant(s) == 3 && tile_kernel_fits(s)) {
       return launch_tile<kDown>(s, dn, tab, groups, scratch.plan, stream);
-    } else if (use_splitk_down(s)) {
+    } else if (down_variant(s) == 2) {
+      hipLaunchKernelGGL((ffn_stream_kernel<kDownHalves, 4, 1>), dim3(s.H / (kWaves * 16), groups.n, (s.T + 63) / 64),
+                         dim3(kThreads), 0, stream, dn, tab, groups);
+    } else if (down_variant(s) == 1) {
       const int tok_blocks = (s.T + kSplitTok - 1) / kSplitTok;
       hipLaunchKernelGGL(ffn_down_splitk_kernel, dim3(s.H / kSplitRows, groups.n, tok_blocks),
                          dim3(kThreads), 0, stream, dn, tab, groups);
