@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel from hardware counters (FETCH_SIZE and
 # WRITE_SIZE, scaled by what the same counters read for a plain copy of known size);
 # measured offline, see profiles/gate_up_c2_mixtral_b64_hbm_traffic.md.
-MEASURED_TRAFFIC_BYTES = {("c2_mixtral", 64): 1900405248}
+MEASURED_TRAFFIC_BYTES = {("c2_mixtral", 64, "row_major"): 1900405248}
 
 
 def parse():
@@ -50,6 +50,8 @@ def parse():
                     help="c5_stack: distinct layers' weights; layer l uses set l %% period")
     ap.add_argument("--c5-steps", type=int, default=16)
     ap.add_argument("--c5-layers", type=int, default=32)
+    ap.add_argument("--layout", default="tiled", choices=["tiled", "row_major"],
+                    help="expert weight layout in HBM (tiled = packed once at load time)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--probe", action="store_true",
                     help="also time a plain 1 GiB copy and a 4 GiB read (achievable HBM rate)")
@@ -111,7 +113,7 @@ def run_c5(args, torch, B):
 
     cfg = get_config("c5_stack")
     NL, NS, T, E = args.c5_layers, args.c5_steps, cfg.T, cfg.E
-    sh = B.make_shape(T, cfg.H, E, cfg.k, cfg.F, cfg.S, cfg.dtype)
+    sh = B.make_shape(T, cfg.H, E, cfg.k, cfg.F, cfg.S, cfg.dtype, args.layout)
     P = min(args.weight_period, NL)
     hosts = [make_layer(cfg, layer=p, with_hidden=False, threads=16) for p in range(P)]
     res = [make_residency_mask(cfg, l) for l in range(NL)]
@@ -194,7 +196,8 @@ def run_c5(args, torch, B):
         "ms_per_step": t_wall / NS * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"c5_stack: {NL} layers x {NS} decode steps, T={T}, weights repeat "
-                               f"with period {P} layers, 2 on-demand + 2x2 prefetch slots"},
+                               f"with period {P} layers, 2 on-demand + 2x2 prefetch slots, "
+                               f"{args.layout} weight layout"},
         "overlap": {
             "T_c_s": t_c, "T_x_s": t_x, "T_wall_s": t_wall, "T_wall_sync_s": t_sync,
             "hidden_literal_A": 1.0 - (t_wall - t_c) / t_x if t_x > 0 else None,
@@ -240,7 +243,7 @@ def main():
     cfg = get_config(args.workload)
     T = args.tokens if args.workload == "c2_mixtral" else cfg.T
     cfg = cfg.with_(T=T)
-    sh = B.make_shape(T, cfg.H, cfg.E, cfg.k, cfg.F, cfg.S, cfg.dtype)
+    sh = B.make_shape(T, cfg.H, cfg.E, cfg.k, cfg.F, cfg.S, cfg.dtype, args.layout)
 
     def dev(a):
         t = torch.from_numpy(a.view(np.int16)).view(torch.bfloat16) if a.dtype == np.uint16 \
@@ -253,6 +256,8 @@ def main():
         if i == 0:
             hosts.append(L)
         Wg, Wu, Wd = dev(L["Wg"]), dev(L["Wu"]), dev(L["Wd"])
+        if args.layout == "tiled":   # the one-time load-time re-layout, outside the timed region
+            Wg, Wu, Wd = B.pack_experts(Wg), B.pack_experts(Wu), B.pack_experts(Wd)
         layers.append(B.make_layer_desc(sh, dev(L["Wr"]), dev(L["b"]), dev=(Wg, Wu, Wd), layer_id=i))
         del L
     Xh = make_hidden(cfg, step=0, T=T)
@@ -313,11 +318,11 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{args.workload} single MoE layer, T={T} decode tokens, "
                                f"H={cfg.H} E={cfg.E} top-{cfg.k} F={cfg.F} S={cfg.S}, all experts "
-                               f"resident, {len(layers)} weight sets rotated",
+                               f"resident ({args.layout} weight layout), {len(layers)} weight sets rotated",
                    "tokens": T, "active_experts": float(np.mean(used))},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, T)),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, T, args.layout)),
                      "kernel": "ffn_stream_kernel<gate/up>", "kernel_ms": gu_ms,
                      "algorithmic_bytes": gu_bytes},
         "phases_ms": {k: ph[k] / max(1, ph["n_layers"]) for k in

@@ -26,7 +26,8 @@
  *  - Storage dtype MOE_BF16: X, Wr and expert matrices are bfloat16, products
  *    are accumulated in float32 (router: float64), `out` is bfloat16.
  *    MOE_F32: everything float32 (router accumulates in float64).
- *  - Row-major layouts.  X [T,H]; Wr [E,H]; Wg, Wu [F,H]; Wd [H,F].
+ *  - X [T,H] and Wr [E,H] are row-major.  Wg, Wu [F,H] and Wd [H,F] are
+ *    row-major or tiled, see moe_weight_layout.
  *  - A = T*k routed assignments, flat id i = t*k + j.  Shared experts (S of
  *    them) see every token with weight one and are not part of the gate.
  *  - Every entry point returns MOE_OK or a negative moe_status; nothing throws
@@ -58,6 +59,19 @@ typedef enum {
 
 typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
 
+/* Memory layout of the expert matrices (the paper fixes none; Section 4.4 only
+ * names gate_proj, up_proj, down_proj).
+ * MOE_ROW_MAJOR: Wg, Wu [F,H] and Wd [H,F] row-major.
+ * MOE_TILED (MOE_BF16 only): every 16-row x 32-column block of a matrix
+ *   [N,K] is one contiguous KiB -- block (n16, ks) at element offset
+ *   (n16*(K/32) + ks)*512; inside it lane l = r + 16 g holds
+ *   W[16 n16 + r][32 ks + 8 g .. 8 g + 7] at element offset 8 l.  That is the
+ *   register image of the matrix-core operand, so a wavefront reads 1 KiB in a
+ *   row per load instead of 16 rows x 64 bytes.  moe_pack_weights() converts;
+ *   it is meant to run once, when an expert is loaded.  Same size in bytes, so
+ *   slots, host copies and transfers are unaffected. */
+typedef enum { MOE_ROW_MAJOR = 0, MOE_TILED = 1 } moe_weight_layout;
+
 /* Problem shape of one call.  T may change from call to call. */
 typedef struct {
   int32_t T;      /* tokens                               */
@@ -67,6 +81,7 @@ typedef struct {
   int32_t F;      /* expert FFN width                     */
   int32_t S;      /* shared (always-on) experts           */
   int32_t dtype;  /* moe_dtype                            */
+  int32_t weight_layout; /* moe_weight_layout of Wg, Wu, Wd (not of Wr, X) */
 } moe_shape;
 
 /* The three matrices of one expert (Section 4.4). */
@@ -118,6 +133,11 @@ moe_status moe_route(const moe_shape* shape, const void* X, const void* Wr,
 moe_status moe_permute(const moe_shape* shape, const int32_t* topk_idx,
                        int32_t* count, int32_t* offset, int32_t* perm,
                        int32_t* inv_perm, void* stream);
+
+/* Re-layout of one bf16 matrix [N,K] (row-major, device) into MOE_TILED form
+ * (device, a different buffer of the same size).  N a multiple of 16, K of 32.
+ * Not a hot call. */
+moe_status moe_pack_weights(const void* src, void* dst, int32_t N, int32_t K, void* stream);
 
 /* ---- a4: grouped SiLU-gated expert FFN over the active experts -----------
  * Section 4.4's three matrices per expert.  For every expert e < E whose bit is

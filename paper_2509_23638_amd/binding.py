@@ -16,6 +16,7 @@ import torch
 from .build import LIB
 
 MOE_F32, MOE_BF16 = 0, 1
+MOE_ROW_MAJOR, MOE_TILED = 0, 1
 MOE_OPT_SYNC_COPIES, MOE_OPT_COPY_SPLIT = 0, 1
 STATUS = {0: "MOE_OK", -1: "MOE_ERR_INVALID_ARG", -2: "MOE_ERR_UNSUPPORTED",
           -3: "MOE_ERR_WORKSPACE", -4: "MOE_ERR_HIP", -5: "MOE_ERR_SLOT_EXHAUSTED"}
@@ -29,7 +30,8 @@ class MoEError(RuntimeError):
 
 class moe_shape(C.Structure):
     _fields_ = [("T", C.c_int32), ("H", C.c_int32), ("E", C.c_int32), ("k", C.c_int32),
-                ("F", C.c_int32), ("S", C.c_int32), ("dtype", C.c_int32)]
+                ("F", C.c_int32), ("S", C.c_int32), ("dtype", C.c_int32),
+                ("weight_layout", C.c_int32)]
 
 
 class moe_expert_ptrs(C.Structure):
@@ -89,19 +91,20 @@ _lib.moe_phase_times_get.argtypes = [_P, C.POINTER(moe_phase_times), C.c_int32]
 _lib.moe_probe_copy.argtypes = [_P, _P, C.c_size_t, _P]
 _lib.moe_probe_read.argtypes = [_P, C.c_size_t, _P, _P]
 _lib.moe_set_option.argtypes = [_P, C.c_int32, C.c_int64]
+_lib.moe_pack_weights.argtypes = [_P, _P, C.c_int32, C.c_int32, _P]
 _lib.moe_rmsnorm.argtypes = [_SH, _P, _P, C.c_float, _P]
 _lib.moe_workspace_views.argtypes = [_SH, _P] + [C.POINTER(_P)] * 7
 for _n in ("moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_create",
            "moe_destroy", "moe_layer_forward", "moe_stream_totals_get", "moe_workspace_views",
            "moe_phase_timing", "moe_phase_times_get", "moe_probe_copy", "moe_probe_read",
-           "moe_rmsnorm", "moe_set_option"):
+           "moe_rmsnorm", "moe_set_option", "moe_pack_weights"):
     getattr(_lib, _n).restype = C.c_int32
 
 EXPORTS = ["moe_version", "moe_last_error", "moe_workspace_bytes", "moe_route", "moe_permute",
            "moe_grouped_ffn", "moe_combine", "moe_create", "moe_destroy", "moe_layer_forward",
            "moe_stream_totals_get", "moe_workspace_views", "moe_phase_timing",
            "moe_phase_times_get", "moe_probe_copy", "moe_probe_read", "moe_rmsnorm",
-           "moe_set_option"]
+           "moe_set_option", "moe_pack_weights"]
 
 
 def _check(st: int):
@@ -118,8 +121,13 @@ def moe_last_error() -> str:
 
 
 # ------------------------------------------------------------ marshalling ---
-def make_shape(T, H, E, k, F, S=0, dtype="bf16") -> moe_shape:
-    return moe_shape(T, H, E, k, F, S, MOE_F32 if dtype in ("f32", MOE_F32) else MOE_BF16)
+def make_shape(T, H, E, k, F, S=0, dtype="bf16", layout="row_major") -> moe_shape:
+    return moe_shape(T, H, E, k, F, S, MOE_F32 if dtype in ("f32", MOE_F32) else MOE_BF16,
+                     MOE_TILED if layout in ("tiled", MOE_TILED) else MOE_ROW_MAJOR)
+
+
+def with_T(shape: moe_shape, T: int) -> moe_shape:
+    return moe_shape(T, shape.H, shape.E, shape.k, shape.F, shape.S, shape.dtype, shape.weight_layout)
 
 
 def _ptr(t: Optional[torch.Tensor], what: str, dtypes=None, numel=None) -> Optional[int]:
@@ -320,6 +328,23 @@ def moe_layer_forward(ctx: Context, shape, layer: Layer, X, out, workspace, resi
         _ptr(workspace, "workspace", (torch.uint8,), moe_workspace_bytes(shape)),
         _stream(stream), C.byref(stats) if stats is not None else None))
     return stats.as_dict() if stats is not None else None
+
+
+def moe_pack_weights(src: torch.Tensor, dst: torch.Tensor, N: int, K: int, stream=None):
+    """One [N,K] bf16 matrix, row-major -> tiled."""
+    bf = (torch.bfloat16, torch.int16, torch.uint16)
+    _check(_lib.moe_pack_weights(_ptr(src, "src", bf, N * K), _ptr(dst, "dst", bf, N * K), N, K,
+                                 _stream(stream)))
+
+
+def pack_experts(W: torch.Tensor) -> torch.Tensor:
+    """[n, N, K] row-major expert matrices -> the same tensor shape holding each
+    matrix in tiled form (a new tensor)."""
+    out = torch.empty_like(W)
+    n, N, K = W.shape
+    for e in range(n):
+        moe_pack_weights(W[e], out[e], N, K)
+    return out
 
 
 def moe_rmsnorm(shape, X, out, eps=1e-6, stream=None):

@@ -19,6 +19,10 @@ moe_status check_shape(const moe_shape* s, const char* who) {
   if (!s) return fail(MOE_ERR_INVALID_ARG, "%s: NULL shape", who);
   if (s->dtype != MOE_F32 && s->dtype != MOE_BF16)
     return fail(MOE_ERR_INVALID_ARG, "%s: unknown dtype %d", who, s->dtype);
+  if (s->weight_layout != MOE_ROW_MAJOR && s->weight_layout != MOE_TILED)
+    return fail(MOE_ERR_INVALID_ARG, "%s: unknown weight layout %d", who, s->weight_layout);
+  if (s->weight_layout == MOE_TILED && s->dtype != MOE_BF16)
+    return fail(MOE_ERR_INVALID_ARG, "%s: the tiled weight layout exists for bf16 storage only", who);
   if (s->T < 0 || s->H <= 0 || s->F <= 0 || s->E <= 0 || s->k <= 0 || s->S < 0)
     return fail(MOE_ERR_INVALID_ARG, "%s: non-positive dimension (T=%d H=%d E=%d k=%d F=%d S=%d)",
                 who, s->T, s->H, s->E, s->k, s->F, s->S);

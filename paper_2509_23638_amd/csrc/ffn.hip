@@ -54,7 +54,18 @@ struct FfnArgs {
   int T, k, E, A;
   int K;                  // contraction length
   int N;                  // output width
+  int tiled;              // weights are in the tiled layout (see moe_weight_layout)
 };
+
+// Element offset of the 16 bytes lane (r, g) feeds the MFMA with for weight tile
+// n16 (rows 16 n16 ..), k-step ks, and the element stride from one k-step to
+// the next.  Row-major: row (16 n16 + r), columns 32 ks + 8 g.  Tiled: the
+// tile is one contiguous KiB and the lane's share sits at 8 * lane.
+__device__ __forceinline__ size_t weight_lane_offset(bool tiled, int n16, int K, int lane) {
+  return tiled ? (size_t)n16 * (K / kKStep) * 512 + (size_t)lane * 8
+               : (size_t)(n16 * 16 + (lane & 15)) * K + (size_t)(lane >> 4) * 8;
+}
+__device__ __forceinline__ int weight_kstep_stride(bool tiled) { return tiled ? 512 : kKStep; }
 
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
 
@@ -81,6 +92,7 @@ struct Streamer {
   const uint16_t* w[NA];  // this lane's first element in each weight tile
   unsigned char* lds;
   int lane, wave;
+  int wstep;              // elements from one k-step of a weight tile to the next
   size_t act_off[NT];     // element offset of this lane's activation row per tile
   static constexpr int NS = (RT == 1 && !kHalves) ? 3 : 2;   // weight chunks held: c .. c+NS-1
   bf16x8 wreg[NS][kStepsPerChunk][NA];
@@ -95,7 +107,8 @@ struct Streamer {
     for (int s = 0; s < kStepsPerChunk; ++s)
 #pragma unroll
       for (int i = 0; i < NA; ++i)
-        wreg[SET][s][i] = *reinterpret_cast<const bf16x8*>(w[i] + (size_t)c * kChunk + s * kKStep);
+        wreg[SET][s][i] = *reinterpret_cast<const bf16x8*>(
+            w[i] + (size_t)(c * kStepsPerChunk + s) * wstep);
   }
 
   // wave w fetches k-step w of every tile of chunk c
@@ -199,18 +212,20 @@ __device__ __forceinline__ void ffn_block(const FfnArgs& a, const uint16_t* W0, 
   st.wave = threadIdx.x / MOE_WAVE;
   const int r = st.lane & 15, g = st.lane >> 4;
   int nrow[NA];  // first output row of each of this wave's weight tiles
+  st.wstep = weight_kstep_stride(a.tiled);
 #pragma unroll
   for (int i = 0; i < NA; ++i) {
     if (MODE == kGateUp) {
       nrow[i] = n0 + (st.wave * RT + (i >> 1)) * 16;
-      st.w[i] = ((i & 1) ? W1 : W0) + (size_t)(nrow[i] + r) * a.K + g * 8;
+      st.w[i] = ((i & 1) ? W1 : W0) + weight_lane_offset(a.tiled, nrow[i] / 16, a.K, st.lane);
     } else if (MODE == kDownHalves) {
       st.half_chunks = a.K / kChunk / 2;
       nrow[i] = n0 + st.wave * 16;
-      st.w[i] = W0 + (size_t)(nrow[i] + r) * a.K + g * 8 + (size_t)i * st.half_chunks * kChunk;
+      st.w[i] = W0 + weight_lane_offset(a.tiled, nrow[i] / 16, a.K, st.lane) +
+                (size_t)i * st.half_chunks * kStepsPerChunk * st.wstep;
     } else {
       nrow[i] = n0 + (st.wave * NA + i) * 16;
-      st.w[i] = W0 + (size_t)(nrow[i] + r) * a.K + g * 8;
+      st.w[i] = W0 + weight_lane_offset(a.tiled, nrow[i] / 16, a.K, st.lane);
     }
   }
 #pragma unroll
@@ -328,12 +343,6 @@ __global__ __launch_bounds__(kThreads) void ffn_stream_kernel(FfnArgs a, ExpertT
 // block is still shared evenly; tiles past the bucket's end are fetched
 // (clamped rows) but not multiplied.  Work items are dealt so that each XCD
 // (own L2) gets a contiguous run of them.
-#ifdef MOE_TILE_TIMING
-__device__ unsigned long long g_tile_ts[8];
-#define TILE_T() clock64()
-#else
-#define TILE_T() 0ull
-#endif
 constexpr int kTileRows = 256;                    // bucket rows per workgroup
 constexpr int kTileK = 64;                        // contraction depth of a stage
 constexpr int kDblFrag = 2 * kFragBytes;          // 16 rows x 64 k
@@ -407,6 +416,21 @@ __device__ __forceinline__ void ffn_tile_block(const FfnArgs& a, const ExpertTab
       const int chunk = slot ^ (u ? ((row8 + 1) & 7) : row8);
       const int rr = 8 * u + row8;   // row inside the 16-row block
       const uint16_t* rowp;
+      if (blk >= 16 && a.tiled) {
+        // tiled weights: fetch u is the MFMA tile of k-step 2 st + u, one KiB in a row
+        const int j = blk - 16;
+        const uint16_t* W;
+        int n16;
+        if (MODE == kGateUp) {
+          W = static_cast<const uint16_t*>(j < 4 ? tab.Wg[e] : tab.Wu[e]);
+          n16 = n0 / 16 + (j & 3);
+        } else {
+          W = static_cast<const uint16_t*>(tab.Wd[e]);
+          n16 = n0 / 16 + j;
+        }
+        src[q] = W + weight_lane_offset(true, n16, a.K, lane) + (size_t)u * 512;
+        continue;
+      }
       if (blk < 16) {
         const int p = min(r0 + blk * 16 + rr, row_end - 1);
         int row;
@@ -425,12 +449,16 @@ __device__ __forceinline__ void ffn_tile_block(const FfnArgs& a, const ExpertTab
       src[q] = rowp + chunk * 8;
     }
   }
+  // elements a source pointer advances per 64-wide stage: 64 along its row,
+  // or two KiB tiles for tiled weights (fetches 4.. of a wave are weights when
+  // h >= 32, i.e. q >= 8)
+  const int w_adv = a.tiled ? 1024 : kTileK;
   auto fetch = [&](int st) {
     unsigned char* base = ring + (st % kTileStages) * kTileStage;
 #pragma unroll
     for (int q = 0; q < kFetchPerWave; ++q)
       __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(src[q] + (size_t)st * kTileK),
+          (const __attribute__((address_space(1))) void*)(src[q] + (size_t)st * (q >= 8 ? w_adv : kTileK)),
           (__attribute__((address_space(3))) void*)(base + (wave + 4 * q) * kFragBytes), 16, 0, 0);
   };
   // where lane (r, g) finds row r, chunk 4 s + g of a block, for k-step s = 0, 1
@@ -441,6 +469,10 @@ __device__ __forceinline__ void ffn_tile_block(const FfnArgs& a, const ExpertTab
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) rd[ks] = u * kFragBytes + (row8 * 8 + ((4 * ks + g) ^ sw)) * 16;
   }
+  // tiled weights arrive as whole MFMA tiles: k-step ks is the ks-th KiB of the block
+  int rdw[2];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) rdw[ks] = a.tiled ? ks * kFragBytes + lane * 16 : rd[ks];
 
   f32x4 acc[4][NJ];   // this wave's token tiles are wm, wm + 2, ...
 #pragma unroll
@@ -449,26 +481,14 @@ __device__ __forceinline__ void ffn_tile_block(const FfnArgs& a, const ExpertTab
     for (int j = 0; j < NJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   const int ns = a.K / kTileK;
-#ifdef MOE_TILE_TIMING
-  unsigned long long t_wait = 0, t_bar = 0, t_mma = 0, t_all = TILE_T();
-#endif
   fetch(0);
   if (ns > 1) fetch(1);
   for (int st = 0; st < ns; ++st) {
-#ifdef MOE_TILE_TIMING
-    const unsigned long long t0 = TILE_T();
-#endif
     // this wave's fetches of stage st have landed once at most the fetches of
     // the one younger stage already issued are still outstanding
     if (st + 1 < ns) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#ifdef MOE_TILE_TIMING
-    const unsigned long long t1 = TILE_T();
-#endif
     __syncthreads();   // everybody's fetches of stage st landed; stage st-1 has been consumed
-#ifdef MOE_TILE_TIMING
-    const unsigned long long t2 = TILE_T();
-#endif
     if (st + 2 < ns) fetch(st + 2);   // into the buffer stage st-1 used
     const unsigned char* base = ring + (st % kTileStages) * kTileStage;
 #pragma unroll
@@ -480,7 +500,7 @@ __device__ __forceinline__ void ffn_tile_block(const FfnArgs& a, const ExpertTab
         int blk;
         if (MODE == kGateUp) blk = 16 + (i >> 1) * 4 + wn * 2 + (i & 1);
         else blk = 16 + wn * 4 + i;
-        wf[i] = *reinterpret_cast<const bf16x8*>(base + blk * kDblFrag + rd[ks]);
+        wf[i] = *reinterpret_cast<const bf16x8*>(base + blk * kDblFrag + rdw[ks]);
       }
 #pragma unroll
       for (int j = 0; j < NJ; ++j)
@@ -492,19 +512,7 @@ __device__ __forceinline__ void ffn_tile_block(const FfnArgs& a, const ExpertTab
         for (int i = 0; i < 4; ++i)
           acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[i], tf[j], acc[i][j], 0, 0, 0);
     }
-#ifdef MOE_TILE_TIMING
-    asm volatile("s_nop 0" ::: "memory");
-    const unsigned long long t3 = TILE_T();
-    t_wait += t1 - t0; t_bar += t2 - t1; t_mma += t3 - t2;
-#endif
   }
-#ifdef MOE_TILE_TIMING
-  if (blockIdx.x == 64 && (threadIdx.x & 63) == 0) {
-    const int w_ = threadIdx.x >> 6;
-    if (w_ == 0) { g_tile_ts[0] = t_wait; g_tile_ts[1] = t_bar; g_tile_ts[2] = t_mma; g_tile_ts[3] = TILE_T() - t_all; g_tile_ts[4] = ns; g_tile_ts[5] = NJ; }
-    if (w_ == 3) { g_tile_ts[6] = t_wait; g_tile_ts[7] = t_bar; }
-  }
-#endif
 
   // D layout: lane holds rows 4*g .. 4*g+3 of the 16-row weight tile, column r = token
   const int r = lane & 15, g = lane >> 4;
@@ -560,15 +568,6 @@ __global__ __launch_bounds__(kThreads, 1) void ffn_tile_kernel(FfnArgs a, Expert
   else ffn_tile_block<MODE, 8>(a, tab, e, r0, row_end, slab, ring);
 }
 
-#ifdef MOE_TILE_TIMING
-}  // namespace
-}  // namespace moe
-extern "C" int moe_debug_tile_ts(unsigned long long* out8) {
-  return (int)hipMemcpyFromSymbol(out8, HIP_SYMBOL(moe::g_tile_ts), 64);
-}
-namespace moe {
-namespace {
-#endif
 
 // Upper bound on the number of 256-row blocks a launch can need.
 int max_row_blocks(const moe_shape& s) {
@@ -607,6 +606,7 @@ struct SplitKStreamer {
   const uint16_t* w0;
   const uint16_t* w1;
   const uint16_t* b[NT];  // this lane's activation row (at its k-group) per tile
+  int wstep;
   bf16x8 wreg[2][kStepsPerChunk][2];
   bf16x8 breg[2][NT][kStepsPerChunk];
   f32x4 acc0[NT], acc1[NT];
@@ -620,8 +620,8 @@ struct SplitKStreamer {
         breg[SET][t][s] = *reinterpret_cast<const bf16x8*>(b[t] + (size_t)c * kChunk + s * kKStep);
 #pragma unroll
     for (int s = 0; s < kStepsPerChunk; ++s) {
-      wreg[SET][s][0] = *reinterpret_cast<const bf16x8*>(w0 + (size_t)c * kChunk + s * kKStep);
-      wreg[SET][s][1] = *reinterpret_cast<const bf16x8*>(w1 + (size_t)c * kChunk + s * kKStep);
+      wreg[SET][s][0] = *reinterpret_cast<const bf16x8*>(w0 + (size_t)(c * kStepsPerChunk + s) * wstep);
+      wreg[SET][s][1] = *reinterpret_cast<const bf16x8*>(w1 + (size_t)(c * kStepsPerChunk + s) * wstep);
     }
   }
 
@@ -664,8 +664,9 @@ __device__ __forceinline__ void down_splitk_block(const FfnArgs& a, const uint16
   const int lane = threadIdx.x & (MOE_WAVE - 1), wave = threadIdx.x / MOE_WAVE;
   const int r = lane & 15, g = lane >> 4;
   SplitKStreamer<NT> st;
-  st.w0 = Wd + (size_t)(n0 + r) * a.K + g * 8;
-  st.w1 = Wd + (size_t)(n0 + 16 + r) * a.K + g * 8;
+  st.wstep = weight_kstep_stride(a.tiled);
+  st.w0 = Wd + weight_lane_offset(a.tiled, n0 / 16, a.K, lane);
+  st.w1 = Wd + weight_lane_offset(a.tiled, n0 / 16 + 1, a.K, lane);
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
     const int p = min(r0 + t * 16 + r, row_end - 1);
@@ -833,7 +834,8 @@ moe_status launch_ffn_gate_up(const moe_shape& s, const void* X, const int32_t* 
   const int A = s.T * s.k;
   void* h = scratch.h;
   if (s.dtype == MOE_BF16) {
-    FfnArgs gu{static_cast<const uint16_t*>(X), perm, offset, h, s.T, s.k, s.E, A, s.H, s.F};
+    FfnArgs gu{static_cast<const uint16_t*>(X), perm, offset, h, s.T, s.k, s.E, A, s.H, s.F,
+               s.weight_layout == MOE_TILED};
     const int v = block_variant(s);
     if (v == 3 && tile_kernel_fits(s)) {
       return launch_tile<kGateUp>(s, gu, tab, groups, scratch.plan, stream);
@@ -866,7 +868,8 @@ moe_status launch_ffn_down(const moe_shape& s, const FfnScratch& scratch, const 
   const int A = s.T * s.k;
   const void* h = scratch.h;
   if (s.dtype == MOE_BF16) {
-    FfnArgs dn{static_cast<const uint16_t*>(h), perm, offset, Y, s.T, s.k, s.E, A, s.F, s.H};
+    FfnArgs dn{static_cast<const uint16_t*>(h), perm, offset, Y, s.T, s.k, s.E, A, s.F, s.H,
+               s.weight_layout == MOE_TILED};
     if (block_variant(s) == 3 && tile_kernel_fits(s)) {
       return launch_tile<kDown>(s, dn, tab, groups, scratch.plan, stream);
     } else if (down_variant(s) == 2) {

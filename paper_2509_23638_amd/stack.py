@@ -48,8 +48,19 @@ class StreamedStack:
         for p, L in enumerate(layers_host):
             dev = {n: [None] * (E + S) for n in ("Wg", "Wu", "Wd")}
             pin = {n: [None] * (E + S) for n in ("Wg", "Wu", "Wd")}
+            tiled = shape.weight_layout == B.MOE_TILED
             for e in range(E + S):
                 ts = [_to_torch(L[n][e]) for n in ("Wg", "Wu", "Wd")]
+                if tiled:
+                    # pack once at load time, on the device; host copies hold the packed bytes
+                    packed = []
+                    for t in ts:
+                        d = t.cuda()
+                        o = torch.empty_like(d)
+                        B.moe_pack_weights(d, o, t.shape[0], t.shape[1])
+                        packed.append(o)
+                    torch.cuda.synchronize()
+                    ts = packed
                 if need_dev[p][e]:
                     for n, t in zip(("Wg", "Wu", "Wd"), ts):
                         dev[n][e] = t.cuda()

@@ -22,8 +22,21 @@ def B():
     return b
 
 
-def _shape(B, cfg, T=None):
-    return B.make_shape(cfg.T if T is None else T, cfg.H, cfg.E, cfg.k, cfg.F, cfg.S, cfg.dtype)
+def _shape(B, cfg, T=None, layout="row_major"):
+    return B.make_shape(cfg.T if T is None else T, cfg.H, cfg.E, cfg.k, cfg.F, cfg.S, cfg.dtype,
+                        layout if cfg.dtype == "bf16" else "row_major")
+
+
+def _experts_dev(B, L, layout):
+    """Expert matrices on the GPU in the requested layout (tiled = packed once
+    by the library, the way a loader would)."""
+    Wg, Wu, Wd = to_dev(L["Wg"]), to_dev(L["Wu"]), to_dev(L["Wd"])
+    if layout == "tiled" and L["Wg"].dtype == np.uint16:
+        Wg, Wu, Wd = B.pack_experts(Wg), B.pack_experts(Wu), B.pack_experts(Wd)
+    return Wg, Wu, Wd
+
+
+LAYOUTS = ["row_major", "tiled"]
 
 
 def _small(name, **kw):
@@ -165,13 +178,13 @@ def test_permute_drops_out_of_range_indices(B):
     assert np.array_equal(invh[want], np.arange(nv))
 
 
-def _ffn_and_combine(B, cfg, L, mask=None):
+def _ffn_and_combine(B, cfg, L, mask=None, layout="row_major"):
     """route/bucket on the CPU oracle, FFN + combine on the GPU."""
-    sh = _shape(B, cfg)
+    sh = _shape(B, cfg, layout=layout)
     ridx, rw, _ = O.route(L["X"], L["Wr"], L["b"], cfg.k)
     count, offset, perm, inv = O.bucket_by_expert(ridx, cfg.E)
     rows = cfg.A + cfg.S * cfg.T
-    Wg, Wu, Wd = to_dev(L["Wg"]), to_dev(L["Wu"]), to_dev(L["Wd"])
+    Wg, Wu, Wd = _experts_dev(B, L, layout)
     tab = B.expert_table(sh, Wg, Wu, Wd)
     Y = torch.full((rows, cfg.H), float("nan"), dtype=torch.float32, device="cuda")
     ws = B.alloc_workspace(sh)
@@ -182,10 +195,13 @@ def _ffn_and_combine(B, cfg, L, mask=None):
     return sh, Y, Yref, (ridx, rw, count, offset, perm, inv), X
 
 
+@pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("cfg", SMALL, ids=lambda c: c.name)
-def test_grouped_ffn_and_combine_small(B, cfg):
+def test_grouped_ffn_and_combine_small(B, cfg, layout):
+    if layout == "tiled" and cfg.dtype != "bf16":
+        pytest.skip("the tiled layout exists for bf16 storage only")
     L = make_layer(cfg)
-    sh, Y, Yref, (ridx, rw, count, offset, perm, inv), X = _ffn_and_combine(B, cfg, L)
+    sh, Y, Yref, (ridx, rw, count, offset, perm, inv), X = _ffn_and_combine(B, cfg, L, layout=layout)
     Yh = Y.cpu().numpy()
     assert np.isfinite(Yh).all()
     assert row_rel_err(Yh, Yref) <= TOL[cfg.dtype]
@@ -219,12 +235,12 @@ def test_grouped_ffn_mask_leaves_rows_untouched(B):
             assert np.isnan(Yh[lo:hi]).all()
 
 
-def _layer_gpu(B, cfg, L, ctx=None, **kw):
-    sh = _shape(B, cfg, L["X"].shape[0])
+def _layer_gpu(B, cfg, L, ctx=None, layout="row_major", dev_weights=None, **kw):
+    sh = _shape(B, cfg, L["X"].shape[0], layout=layout)
     own = ctx is None
     if own:
         ctx = B.Context(sh)
-    Wg, Wu, Wd = to_dev(L["Wg"]), to_dev(L["Wu"]), to_dev(L["Wd"])
+    Wg, Wu, Wd = dev_weights if dev_weights is not None else _experts_dev(B, L, layout)
     layer = B.make_layer_desc(sh, to_dev(L["Wr"]), to_dev(L["b"]), dev=(Wg, Wu, Wd))
     X = to_dev(L["X"])
     out = torch.empty_like(X)
@@ -239,10 +255,13 @@ def _layer_gpu(B, cfg, L, ctx=None, **kw):
     return res
 
 
+@pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("cfg", SMALL, ids=lambda c: c.name)
-def test_layer_forward_small(B, cfg):
+def test_layer_forward_small(B, cfg, layout):
+    if layout == "tiled" and cfg.dtype != "bf16":
+        pytest.skip("the tiled layout exists for bf16 storage only")
     L = make_layer(cfg)
-    got = _layer_gpu(B, cfg, L)
+    got = _layer_gpu(B, cfg, L, layout=layout)
     ref = O.moe_layer(L["X"], L["Wr"], L["b"], L["Wg"], L["Wu"], L["Wd"], cfg.k, cfg.S)
     assert np.array_equal(got["topk_idx"], ref["topk_idx"])
     assert np.abs(got["topk_w"] - ref["topk_w"]).max() <= 1e-5
@@ -259,10 +278,11 @@ def test_layer_forward_c1_tiny(B):
     assert row_rel_err(got["out"], ref["out"]) <= 1e-5
 
 
-def test_layer_forward_c3_finegrained(B):
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_layer_forward_c3_finegrained(B, layout):
     cfg = get_config("c3_finegrained")
     L = make_layer(cfg)
-    got = _layer_gpu(B, cfg, L)
+    got = _layer_gpu(B, cfg, L, layout=layout)
     ref = O.moe_layer(L["X"], L["Wr"], L["b"], L["Wg"], L["Wu"], L["Wd"], cfg.k, cfg.S)
     assert np.array_equal(got["topk_idx"], ref["topk_idx"])
     assert np.abs(got["topk_w"] - ref["topk_w"]).max() <= 1e-5
@@ -270,14 +290,15 @@ def test_layer_forward_c3_finegrained(B):
     assert np.array_equal(got["count"], np.bincount(ref["topk_idx"].reshape(-1), minlength=cfg.E))
 
 
+@pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("T", [64, 1, 8, 256])
-def test_layer_forward_c2_mixtral_sampled(B, T, c2_weights):
+def test_layer_forward_c2_mixtral_sampled(B, T, layout, c2_weights, c2_dev):
     """Full Mixtral-shaped layer in the launch configuration the benchmark
     times; routing checked for every token, outputs for a seeded sample of
     tokens the oracle evaluates one by one."""
     cfg, L = c2_weights
     X = make_hidden(cfg, T=T)
-    got = _layer_gpu(B, cfg, dict(L, X=X))
+    got = _layer_gpu(B, cfg, dict(L, X=X), layout=layout, dev_weights=c2_dev[layout])
     r = np.random.Generator(np.random.PCG64(100 + T))
     sample = sorted(r.choice(T, size=min(T, 6), replace=False).tolist())
     ref = O.moe_layer(X, L["Wr"], L["b"], L["Wg"], L["Wu"], L["Wd"], cfg.k, cfg.S, tokens=sample)
@@ -286,16 +307,59 @@ def test_layer_forward_c2_mixtral_sampled(B, T, c2_weights):
     assert row_rel_err(got["out"][sample], ref["out"][sample]) <= TOL["bf16"]
 
 
+def test_layer_forward_c5_shape_streamed(B, c2_weights, c2_dev):
+    """One layer of the streamed stack at its real shape (Mixtral experts,
+    batch 32): half of the experts come from pinned host memory through the
+    slots, two of them prefetched by an earlier call; the result must equal the
+    all-resident result bit for bit and match the oracle on sampled tokens."""
+    from paper_2509_23638_amd.stack import StreamedStack
+    from workloads import make_residency_mask
+    cfg, L = c2_weights
+    cfg = cfg.with_(T=32)
+    sh = _shape(B, cfg, 32)
+    X = make_hidden(cfg, step=3, T=32)
+    res = make_residency_mask(cfg, 0)
+    ref = O.moe_layer(X, L["Wr"], L["b"], L["Wg"], L["Wu"], L["Wd"], cfg.k, cfg.S, tokens=[0, 9, 31])
+    active = np.bincount(ref["topk_idx"].reshape(-1), minlength=cfg.E) > 0
+    stack = StreamedStack(sh, [L], [res, res], 2, 2, n_layers=2)
+    Xd = to_dev(X)
+    out0, out1 = torch.empty_like(Xd), torch.empty_like(Xd)
+    pf = np.zeros(cfg.E, dtype=bool)
+    pf[[e for e in range(cfg.E) if not res[e] and active[e]][:2]] = True
+    # layer 0: everything non-resident is a miss; it also prefetches two experts for layer 1
+    st0 = stack.layer_forward(0, Xd, out0, prefetch_next_mask=pf, next_l=1)
+    st1 = stack.layer_forward(1, Xd, out1)            # same weights, same input
+    torch.cuda.synchronize()
+    n_nonres = int((active & ~res).sum())
+    assert st0["n_miss"] == n_nonres and st0["n_hit"] == 0 and st0["n_prefetch_issued"] == int(pf.sum())
+    assert st1["n_hit"] == int(pf.sum()) and st1["n_miss"] == n_nonres - int(pf.sum())
+    full = _layer_gpu(B, cfg, dict(L, X=X), dev_weights=c2_dev["row_major"])
+    got0 = O.widen(to_host_bits(out0))
+    assert np.array_equal(got0, full["out"])
+    assert torch.equal(out0.view(torch.int16), out1.view(torch.int16))
+    assert row_rel_err(got0[[0, 9, 31]], ref["out"][[0, 9, 31]]) <= TOL["bf16"]
+    stack.close()
+
+
 @pytest.fixture(scope="module")
 def c2_weights():
     cfg = get_config("c2_mixtral")
     return cfg, make_layer(cfg, with_hidden=False)
 
 
-def test_layer_forward_c4_prefill_sampled(B):
+@pytest.fixture(scope="module")
+def c2_dev(B, c2_weights):
+    """The Mixtral-shaped layer's experts on the GPU, in both layouts."""
+    cfg, L = c2_weights
+    rm = _experts_dev(B, L, "row_major")
+    return {"row_major": rm, "tiled": tuple(B.pack_experts(W) for W in rm)}
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_layer_forward_c4_prefill_sampled(B, layout):
     cfg = get_config("c4_dsv2lite_prefill")
     L = make_layer(cfg)
-    got = _layer_gpu(B, cfg, L)
+    got = _layer_gpu(B, cfg, L, layout=layout)
     r = np.random.Generator(np.random.PCG64(4))
     sample = sorted(r.choice(cfg.T, size=24, replace=False).tolist())
     ref = O.moe_layer(L["X"], L["Wr"], L["b"], L["Wg"], L["Wu"], L["Wd"], cfg.k, cfg.S, tokens=sample)
@@ -324,6 +388,31 @@ def test_empty_batch_and_errors(B):
         B.moe_workspace_bytes(B.make_shape(4, 256, 4, 5, 384))        # k > E
     with pytest.raises(B.MoEError):
         B.moe_workspace_bytes(B.make_shape(4, 256, 200, 2, 384))      # E too large
+
+
+def test_pack_weights_layout(B):
+    """The tiled layout is exactly what the header says: tile (n16, ks) is one
+    KiB, lane l = r + 16 g holds W[16 n16 + r][32 ks + 8 g .. + 7]."""
+    r = np.random.Generator(np.random.PCG64(21))
+    N, K = 48, 96
+    W = r.integers(0, 65536, size=(N, K)).astype(np.uint16)
+    src = to_dev(W)
+    dst = torch.empty_like(src)
+    B.moe_pack_weights(src, dst, N, K)
+    torch.cuda.synchronize()
+    got = to_host_bits(dst).reshape(-1)
+    want = np.empty(N * K, dtype=np.uint16)
+    for n16 in range(N // 16):
+        for ks in range(K // 32):
+            for lane in range(64):
+                rr, g = lane % 16, lane // 16
+                o = ((n16 * (K // 32) + ks) * 64 + lane) * 8
+                want[o:o + 8] = W[16 * n16 + rr, 32 * ks + 8 * g: 32 * ks + 8 * g + 8]
+    assert np.array_equal(got, want)
+    with pytest.raises(B.MoEError):
+        B.moe_pack_weights(src, dst, 40, 96)        # N not a multiple of 16
+    with pytest.raises(B.MoEError):
+        B.moe_workspace_bytes(B.make_shape(4, 72, 4, 2, 40, dtype="f32", layout="tiled"))
 
 
 def test_batch_independence_bitwise(B):

@@ -50,10 +50,11 @@ def _masks(trace, step, kind):
     return res, pf
 
 
+@pytest.mark.parametrize("layout", ["row_major", "tiled"])
 @pytest.mark.parametrize("kind", ["predicted", "none", "wrong"])
-def test_streamed_layers_match_resident_bitwise_and_oracle(B, layers, kind):
+def test_streamed_layers_match_resident_bitwise_and_oracle(B, layers, kind, layout):
     from paper_2509_23638_amd.stack import StreamedStack
-    sh = B.make_shape(CFG.T, CFG.H, CFG.E, CFG.k, CFG.F, CFG.S, CFG.dtype)
+    sh = B.make_shape(CFG.T, CFG.H, CFG.E, CFG.k, CFG.F, CFG.S, CFG.dtype, layout)
     all_res = [[True] * CFG.E for _ in range(CFG.layers)]
     ref_stack = StreamedStack(sh, layers, all_res, 0, 0)
     res0 = [make_residency_mask(CFG, l) for l in range(CFG.layers)]
