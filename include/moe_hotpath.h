@@ -274,16 +274,24 @@ moe_status moe_stream_totals_get(moe_ctx* ctx, moe_stream_totals* out, int32_t r
 typedef enum { MOE_OPT_SYNC_COPIES = 0, MOE_OPT_COPY_SPLIT = 1 } moe_option;
 moe_status moe_set_option(moe_ctx* ctx, int32_t option, int64_t value);
 
-/* Optional per-phase timing of layers whose experts are all resident: when
- * enabled, moe_layer_forward records an event on `stream` before the router
- * and after each of the five kernels (route, permute, gate/up, down, combine);
+/* Optional per-phase timing of layers whose experts are all resident, for
+ * measurement harnesses; off by default.
+ *   mode 1: moe_layer_forward records an event on `stream` before the router
+ *           and after each of the five kernels (route, permute, gate/up, down,
+ *           combine): six markers per layer;
+ *   mode 2: only the two markers around the gate/up kernel (the dominant one),
+ *           which perturbs the layer's own timing the least;
+ *   mode 0: off.
  * moe_phase_times_get waits for the recorded layers and returns the summed
- * durations.  For measurement harnesses; off by default. */
+ * durations: the five phases over `n_layers` mode-1 layers, and
+ * `gate_up_only_ms` over `gate_up_only_layers` mode-2 layers. */
 typedef struct {
   double route_ms, permute_ms, gate_up_ms, down_ms, combine_ms;
   int64_t n_layers;
+  double gate_up_only_ms;
+  int64_t gate_up_only_layers;
 } moe_phase_times;
-moe_status moe_phase_timing(moe_ctx* ctx, int32_t enable);
+moe_status moe_phase_timing(moe_ctx* ctx, int32_t mode);
 moe_status moe_phase_times_get(moe_ctx* ctx, moe_phase_times* out, int32_t reset);
 
 /* Measurement aids (not part of the method): a plain streaming copy

@@ -60,7 +60,8 @@ class moe_stream_totals(C.Structure):
 
 class moe_phase_times(C.Structure):
     _fields_ = [("route_ms", C.c_double), ("permute_ms", C.c_double), ("gate_up_ms", C.c_double),
-                ("down_ms", C.c_double), ("combine_ms", C.c_double), ("n_layers", C.c_int64)]
+                ("down_ms", C.c_double), ("combine_ms", C.c_double), ("n_layers", C.c_int64),
+                ("gate_up_only_ms", C.c_double), ("gate_up_only_layers", C.c_int64)]
 
 
 if not os.path.exists(LIB):
@@ -269,8 +270,9 @@ class Context:
     def set_copy_split(self, n: int):
         _check(_lib.moe_set_option(self._h, MOE_OPT_COPY_SPLIT, n))
 
-    def phase_timing(self, enable: bool):
-        _check(_lib.moe_phase_timing(self._h, 1 if enable else 0))
+    def phase_timing(self, mode):
+        """0/False off, 1/True all five phases, 2 only the gate/up kernel."""
+        _check(_lib.moe_phase_timing(self._h, int(mode)))
 
     def phase_times(self, reset=False) -> dict:
         t = moe_phase_times()

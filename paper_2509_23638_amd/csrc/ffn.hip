@@ -491,27 +491,39 @@ __device__ __forceinline__ void ffn_tile_block(const FfnArgs& a, const ExpertTab
     __syncthreads();   // everybody's fetches of stage st landed; stage st-1 has been consumed
     if (st + 2 < ns) fetch(st + 2);   // into the buffer stage st-1 used
     const unsigned char* base = ring + (st % kTileStages) * kTileStage;
+    // LDS reads of both k-steps are issued up front, in order; the MFMAs of the
+    // first k-step only wait for its own operands (LDS returns in order), so the
+    // second k-step's reads land while the matrix pipe is busy
+    bf16x8 wf[2][4], tf[2][NJ];
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-      // all LDS reads of the k-step are issued before its first MFMA
-      bf16x8 wf[4], tf[NJ];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         int blk;
         if (MODE == kGateUp) blk = 16 + (i >> 1) * 4 + wn * 2 + (i & 1);
         else blk = 16 + wn * 4 + i;
-        wf[i] = *reinterpret_cast<const bf16x8*>(base + blk * kDblFrag + rdw[ks]);
+        wf[ks][i] = *reinterpret_cast<const bf16x8*>(base + blk * kDblFrag + rdw[ks]);
       }
 #pragma unroll
       for (int j = 0; j < NJ; ++j)
-        tf[j] = *reinterpret_cast<const bf16x8*>(base + (wm + 2 * j) * kDblFrag + rd[ks]);
-      __builtin_amdgcn_sched_barrier(0);   // keep the scheduler from sinking the reads again
+        tf[ks][j] = *reinterpret_cast<const bf16x8*>(base + (wm + 2 * j) * kDblFrag + rd[ks]);
+    }
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
       for (int j = 0; j < NJ; ++j)
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[i], tf[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ks][i], tf[ks][j], acc[i][j], 0, 0, 0);
+    // order for the scheduler: the first k-step's reads, then its MFMAs with the
+    // second k-step's reads slipped in one per two MFMAs, then the rest
+    __builtin_amdgcn_sched_group_barrier(0x100, 4 + NJ, 0);
+#pragma unroll
+    for (int q = 0; q < 4 + NJ; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
+    __builtin_amdgcn_sched_group_barrier(0x008, 8 * NJ - 2 * (4 + NJ), 0);
   }
 
   // D layout: lane holds rows 4*g .. 4*g+3 of the 16-row weight tile, column r = token

@@ -69,11 +69,14 @@ struct moe_ctx {
   int copy_split = 1;        // 1: one copy per expert when its matrices are contiguous on the
                              // host; 3: one copy per matrix, first phase gated on gate+up only
   // optional per-phase timing of all-resident layers (6 boundary events each)
-  bool phase_timing = false;
-  std::vector<hipEvent_t> phase_events;  // 6 per timed layer, in call order
+  int phase_timing = 0;      // 0 off, 1 all five phases, 2 only the gate/up phase
+  std::vector<hipEvent_t> phase_events;  // 6 (or 2) per timed layer, in call order
+  std::vector<int> phase_kinds;          // per timed layer: 1 or 2
   std::vector<hipEvent_t> phase_free;
   double phase_ms[5] = {0, 0, 0, 0, 0};
   int64_t phase_layers = 0;
+  double gate_up_only_ms = 0.0;
+  int64_t gate_up_only_layers = 0;
 };
 
 namespace moe {
@@ -356,21 +359,23 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
                   "moe_layer_forward: non-resident expert %d has no pinned host copy", e);
   }
 
-  const bool timed = c->phase_timing && all_resident;
-#define PHASE_MARK()                                   \
-  do {                                                 \
-    if (timed) {                                       \
-      moe_status _p = phase_event(c, stream);          \
-      if (_p != MOE_OK) return _p;                     \
-    }                                                  \
+  const int timed = all_resident ? c->phase_timing : 0;
+  // mark i of the six phase boundaries; mode 2 records only the two around gate/up
+#define PHASE_MARK(i)                                            \
+  do {                                                           \
+    if (timed == 1 || (timed == 2 && ((i) == 2 || (i) == 3))) {  \
+      moe_status _p = phase_event(c, stream);                    \
+      if (_p != MOE_OK) return _p;                               \
+    }                                                            \
   } while (0)
-  PHASE_MARK();
+  if (timed) c->phase_kinds.push_back(timed);
+  PHASE_MARK(0);
   st = launch_route(s, X, layer->Wr, layer->bias, topk_idx, topk_w, nullptr, stream);
   if (st != MOE_OK) return st;
-  PHASE_MARK();
+  PHASE_MARK(1);
   st = launch_permute(s, topk_idx, count, offset, perm, inv_perm, stream);
   if (st != MOE_OK) return st;
-  PHASE_MARK();
+  PHASE_MARK(2);
 
   ExpertTable tab;
   for (int e = 0; e < s.E + s.S; ++e) {
@@ -388,10 +393,10 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
     for (int e = 0; e < s.E + s.S; ++e) res_groups.id[res_groups.n++] = (uint8_t)e;
     st = launch_ffn_gate_up(s, X, perm, offset, tab, res_groups, h, stream);
     if (st != MOE_OK) return st;
-    PHASE_MARK();
+    PHASE_MARK(3);
     st = launch_ffn_down(s, h, perm, offset, tab, res_groups, Y, stream);
     if (st != MOE_OK) return st;
-    PHASE_MARK();
+    PHASE_MARK(4);
   } else {
     // the host must know which experts are active before it can queue copies
     MOE_HIP(hipMemcpyAsync(c->host_counts, count, s.E * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
@@ -483,7 +488,7 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
 
   st = launch_combine(s, Y, topk_w, inv_perm, residual, out, stream);
   if (st != MOE_OK) return st;
-  PHASE_MARK();
+  PHASE_MARK(5);
 #undef PHASE_MARK
 
   // prefetch for the next layer, behind every on-demand copy queued above
@@ -523,34 +528,52 @@ extern "C" moe_status moe_set_option(moe_ctx* c, int32_t option, int64_t value) 
   }
 }
 
-extern "C" moe_status moe_phase_timing(moe_ctx* c, int32_t enable) {
+extern "C" moe_status moe_phase_timing(moe_ctx* c, int32_t mode) {
   MOE_REQUIRE(c, "moe_phase_timing: NULL context");
-  c->phase_timing = enable != 0;
+  MOE_REQUIRE(mode >= 0 && mode <= 2, "moe_phase_timing: mode must be 0, 1 or 2");
+  c->phase_timing = mode;
   return MOE_OK;
 }
 
 extern "C" moe_status moe_phase_times_get(moe_ctx* c, moe_phase_times* out, int32_t reset) {
   MOE_REQUIRE(c && out, "moe_phase_times_get: NULL argument");
-  for (size_t i = 0; i + 6 <= c->phase_events.size(); i += 6) {
-    MOE_HIP(hipEventSynchronize(c->phase_events[i + 5]));
-    for (int p = 0; p < 5; ++p) {
+  size_t at = 0;
+  for (size_t l = 0; l < c->phase_kinds.size(); ++l) {
+    const int kind = c->phase_kinds[l];
+    const size_t n = kind == 1 ? 6 : 2;
+    if (at + n > c->phase_events.size()) break;
+    MOE_HIP(hipEventSynchronize(c->phase_events[at + n - 1]));
+    if (kind == 1) {
+      for (int p = 0; p < 5; ++p) {
+        float ms = 0.f;
+        MOE_HIP(hipEventElapsedTime(&ms, c->phase_events[at + p], c->phase_events[at + p + 1]));
+        c->phase_ms[p] += ms;
+      }
+      c->phase_layers += 1;
+    } else {
       float ms = 0.f;
-      MOE_HIP(hipEventElapsedTime(&ms, c->phase_events[i + p], c->phase_events[i + p + 1]));
-      c->phase_ms[p] += ms;
+      MOE_HIP(hipEventElapsedTime(&ms, c->phase_events[at], c->phase_events[at + 1]));
+      c->gate_up_only_ms += ms;
+      c->gate_up_only_layers += 1;
     }
-    c->phase_layers += 1;
+    at += n;
   }
   for (hipEvent_t e : c->phase_events) c->phase_free.push_back(e);
   c->phase_events.clear();
+  c->phase_kinds.clear();
   out->route_ms = c->phase_ms[0];
   out->permute_ms = c->phase_ms[1];
   out->gate_up_ms = c->phase_ms[2];
   out->down_ms = c->phase_ms[3];
   out->combine_ms = c->phase_ms[4];
   out->n_layers = c->phase_layers;
+  out->gate_up_only_ms = c->gate_up_only_ms;
+  out->gate_up_only_layers = c->gate_up_only_layers;
   if (reset) {
     for (double& v : c->phase_ms) v = 0.0;
     c->phase_layers = 0;
+    c->gate_up_only_ms = 0.0;
+    c->gate_up_only_layers = 0;
   }
   return MOE_OK;
 }
