@@ -46,7 +46,8 @@ def parse():
     ap.add_argument("--weight-sets", type=int, default=3,
                     help="distinct layers' weights rotated through (cache defeat)")
     ap.add_argument("--workload", default="c2_mixtral",
-                    choices=["c2_mixtral", "c3_finegrained", "c4_dsv2lite_prefill", "c5_stack"])
+                    choices=["c2_mixtral", "c3_finegrained", "c4_dsv2lite_prefill", "c5_stack",
+                             "c6_qwen3_a3b"])
     ap.add_argument("--weight-period", type=int, default=4,
                     help="c5_stack: distinct layers' weights; layer l uses set l %% period")
     ap.add_argument("--c5-steps", type=int, default=16)

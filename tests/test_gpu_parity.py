@@ -91,7 +91,8 @@ def test_route_small(B, cfg):
     _check_route(B, cfg, L, L["X"])
 
 
-@pytest.mark.parametrize("name", ["c1_tiny", "c2_mixtral", "c3_finegrained", "c4_dsv2lite_prefill"])
+@pytest.mark.parametrize("name", ["c1_tiny", "c2_mixtral", "c3_finegrained", "c4_dsv2lite_prefill",
+                                  "c6_qwen3_a3b"])
 def test_route_full_size(B, name):
     """Router at the real shapes (router weights only; no expert matrices)."""
     from workloads import make_router
@@ -284,6 +285,21 @@ def test_layer_forward_c3_finegrained(B, layout):
     L = make_layer(cfg)
     got = _layer_gpu(B, cfg, L, layout=layout)
     ref = O.moe_layer(L["X"], L["Wr"], L["b"], L["Wg"], L["Wu"], L["Wd"], cfg.k, cfg.S)
+    assert np.array_equal(got["topk_idx"], ref["topk_idx"])
+    assert np.abs(got["topk_w"] - ref["topk_w"]).max() <= 1e-5
+    assert row_rel_err(got["out"], ref["out"]) <= TOL["bf16"]
+    assert np.array_equal(got["count"], np.bincount(ref["topk_idx"].reshape(-1), minlength=cfg.E))
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_layer_forward_c6_qwen3_a3b(B, layout):
+    """Qwen3-30B-A3B-shaped decode layer (128 experts, top-8, 9 MiB experts):
+    the most fine-grained shape of Table 2, every token against the oracle."""
+    cfg = get_config("c6_qwen3_a3b")
+    L = make_layer(cfg)
+    got = _layer_gpu(B, cfg, L, layout=layout)
+    ref = O.moe_layer(L["X"], L["Wr"], L["b"], L["Wg"], L["Wu"], L["Wd"], cfg.k, cfg.S)
+    assert O.routing_margins(ref["logits"], cfg.k).min() > 1e-9
     assert np.array_equal(got["topk_idx"], ref["topk_idx"])
     assert np.abs(got["topk_w"] - ref["topk_w"]).max() <= 1e-5
     assert row_rel_err(got["out"], ref["out"]) <= TOL["bf16"]

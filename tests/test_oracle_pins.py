@@ -388,6 +388,9 @@ def check_table2_sizes():
     assert c4.expert_bytes == 17301504
     assert (c2.E, c2.k, c5.layers) == (int(rows[0][2]), int(rows[0][3]), int(rows[0][1]))
     assert (c4.E, c4.k) == (int(rows[1][2]), int(rows[1][3]))
+    c6 = get_config("c6_qwen3_a3b")
+    assert c6.expert_bytes == 9 * 2 ** 20
+    assert (c6.E, c6.k, c6.H, c6.F) == tuple(int(rows[3][i]) for i in (2, 3, 5, 6))
 
 
 def check_table3_identity():

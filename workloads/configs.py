@@ -1,4 +1,4 @@
-"""The five synthetic workload shapes.
+"""The synthetic workload shapes.
 
 Shapes follow the evaluated models' expert geometry (paper Table 2: Mixtral-8x7B
 with 8 experts / top-2 / 336 MiB per bf16 expert; DeepSeek-V2-Lite-like with 64
@@ -70,6 +70,10 @@ CONFIGS = {
     "c5_stack": MoEConfig("c5_stack", T=32, H=4096, E=8, k=2, F=14336, S=0,
                           dtype="bf16", bias="normal", bias_scale=0.5,
                           layers=32, steps=16),
+    # widening case: Qwen3-30B-A3B-shaped decode layer (Table 2: 128 experts,
+    # top-8, 9 MiB per bf16 expert = 3 x 2048 x 768 x 2 bytes), batch 64
+    "c6_qwen3_a3b": MoEConfig("c6_qwen3_a3b", T=64, H=2048, E=128, k=8, F=768,
+                              S=0, dtype="bf16", bias="normal", bias_scale=0.5),
 }
 
 
