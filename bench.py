@@ -52,6 +52,19 @@ def parse():
                     help="c5_stack: distinct layers' weights; layer l uses set l %% period")
     ap.add_argument("--c5-steps", type=int, default=16)
     ap.add_argument("--c5-layers", type=int, default=32)
+    ap.add_argument("--c5-policy", default="noisy_top2",
+                    choices=["noisy_top2", "gate_top2", "presched", "none"],
+                    help="c5_stack prefetch policy: noisy copy of the true next-layer logits "
+                         "(default), gate-based prediction, gate-based prediction + PreSched, "
+                         "or on-demand loads only")
+    ap.add_argument("--c5-residency", default="random", choices=["random", "hot"],
+                    help="c5_stack resident experts: seeded 4 of 8 per layer, or the hot-expert "
+                         "table of a profiling pass under the same budget")
+    ap.add_argument("--c5-profile-steps", type=int, default=8)
+    ap.add_argument("--c5-tokens", type=int, default=None,
+                    help="c5_stack batch (default: the configuration's 32)")
+    ap.add_argument("--no-c5-controls", action="store_true",
+                    help="c5_stack: skip the synchronous-copy and three-copies-per-expert reruns")
     ap.add_argument("--layout", default="tiled", choices=["tiled", "row_major"],
                     help="expert weight layout in HBM (tiled = packed once at load time)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -114,12 +127,38 @@ def run_c5(args, torch, B):
     from paper_2509_23638_amd.stack import StreamedStack, noisy_topk_prefetch_mask, _to_torch
 
     cfg = get_config("c5_stack")
+    if args.c5_tokens:
+        cfg = cfg.with_(T=args.c5_tokens)
     NL, NS, T, E = args.c5_layers, args.c5_steps, cfg.T, cfg.E
     sh = B.make_shape(T, cfg.H, E, cfg.k, cfg.F, cfg.S, cfg.dtype, args.layout)
     P = min(args.weight_period, NL)
     hosts = [make_layer(cfg, layer=p, with_hidden=False, threads=16) for p in range(P)]
     res = [make_residency_mask(cfg, l) for l in range(NL)]
     ref = StreamedStack(sh, hosts, [[True] * E] * NL, 0, 0, n_layers=NL)
+    hot_info = None
+    if args.c5_residency == "hot":
+        # Section 4.1: count tokens per (layer, expert) over profiling batches (other
+        # seeds than the timed steps), keep the hottest resident under the same budget
+        total = torch.zeros((NL, E), dtype=torch.int64, device="cuda")
+        views = B.moe_workspace_views(sh, ref.ws)
+        norm = torch.empty((T, cfg.H), dtype=torch.bfloat16, device="cuda")
+        bufs = [torch.empty_like(norm), torch.empty_like(norm)]
+        for s_ in range(args.c5_profile_steps):
+            x = _to_torch(make_hidden(cfg, step=1000 + s_)).cuda()
+            for l in range(NL):
+                B.moe_rmsnorm(sh, x, norm)
+                ref.layer_forward(l, norm, bufs[l & 1], residual=x, want_stats=False)
+                B.moe_counter_add(sh, views["count"], total[l])
+                x = bufs[l & 1]
+        torch.cuda.synchronize()
+        budget = int(sum(int(np.sum(m)) for m in res))
+        tok = total.cpu().numpy()
+        hot = B.moe_hot_table(tok, budget)
+        hot_info = {"budget_experts": budget, "profile_steps": args.c5_profile_steps,
+                    "tokens_covered_by_random_masks": int(sum(tok[l][res[l]].sum() for l in range(NL))),
+                    "tokens_covered_by_hot_table": int(tok[hot].sum()), "tokens_total": int(tok.sum()),
+                    "resident_per_layer_min_max": [int(hot.sum(1).min()), int(hot.sum(1).max())]}
+        res = [hot[l] for l in range(NL)]
     stack = StreamedStack(sh, hosts, res, 2, 2, n_layers=NL)
     Xs = [_to_torch(make_hidden(cfg, step=s)).cuda() for s in range(NS)]
 
@@ -162,12 +201,23 @@ def run_c5(args, torch, B):
         for s in range(NS):
             ref.step(Xs[s], want_stats=False)
 
+    costs = B.moe_presched_costs(t_io=1.0, t_g=0.0, t_attn=0.0, beta=0.0, C=0.0, alpha=0.0,
+                                 r_hit=0.5, cpu_executor=0)
+
     def run_streamed():
         agg = {"n_active": 0, "n_resident": 0, "n_hit": 0, "n_miss": 0, "n_wasted": 0,
                "n_prefetch_issued": 0, "bytes_on_demand": 0, "bytes_prefetch": 0}
         same = True
         for s in range(NS):
-            x, st = stack.step(Xs[s], prefetch_masks=masks[s], wrap_prefetch=True)
+            if args.c5_policy == "noisy_top2":
+                x, st = stack.step(Xs[s], prefetch_masks=masks[s], wrap_prefetch=s + 1 < NS)
+            else:
+                if agg["n_prefetch_issued"]:
+                    # hit rate of the prefetches so far, as the Timer/Counter would report it
+                    costs.r_hit = agg["n_hit"] / agg["n_prefetch_issued"]
+                pol = {"gate_top2": "gate_topn", "presched": "presched", "none": "none"}[args.c5_policy]
+                x, st = stack.step_online(Xs[s], pol, costs=costs, n_prefetch=2,
+                                          wrap_prefetch=False)
             for d in st:
                 for k_ in agg:
                     agg[k_] += d[k_]
@@ -176,30 +226,52 @@ def run_c5(args, torch, B):
 
     run_ref()
     t_c, _ = timed(run_ref)
+    # Timer inputs of PreSched, measured: one layer's compute, one expert's load
+    t_layer = t_c / (NS * NL)
     stack.ctx.stream_totals(reset=True)
+    stack.step(Xs[0], want_stats=False)
+    torch.cuda.synchronize()
+    cal = stack.ctx.stream_totals(reset=True)
+    costs.t_io = cal["copy_ms"] * 1e-3 / max(1, cal["n_copies"])
+    costs.t_g = t_layer / E
+    costs.t_attn = t_layer          # the only time per layer the link has no on-demand work
     t_wall, (agg, same) = timed(run_streamed)
     tot = stack.ctx.stream_totals(reset=True)
     t_x = tot["copy_ms"] * 1e-3
-    stack.ctx.set_sync_copies(True)
-    t_sync, (agg2, same2) = timed(run_streamed)
-    tot2 = stack.ctx.stream_totals(reset=True)
-    stack.ctx.set_sync_copies(False)
-    # Section 4.4's sub-tensor granularity: three copies per expert, phase 1 gated on gate+up
-    stack.ctx.set_copy_split(3)
-    t_wall3, (agg3, same3) = timed(run_streamed)
-    tot3 = stack.ctx.stream_totals(reset=True)
-    stack.ctx.set_copy_split(1)
+    sched_log = dict(stack.sched_log)
+    if args.no_c5_controls:
+        t_sync, same2, tot2 = None, True, {"bytes": 0, "copy_ms": 0.0}
+        t_wall3, same3, tot3 = None, True, {"bytes": 0, "copy_ms": 0.0}
+    else:
+        stack.ctx.set_sync_copies(True)
+        t_sync, (agg2, same2) = timed(run_streamed)
+        tot2 = stack.ctx.stream_totals(reset=True)
+        stack.ctx.set_sync_copies(False)
+        # Section 4.4's sub-tensor granularity: three copies per expert, phase 1 gated on gate+up
+        stack.ctx.set_copy_split(3)
+        t_wall3, (agg3, same3) = timed(run_streamed)
+        tot3 = stack.ctx.stream_totals(reset=True)
+        stack.ctx.set_copy_split(1)
 
     tokens = T * NS
     res_json = {
-        "metric": "streamed MoE stack decode tokens/sec (32-layer Mixtral-shaped stack, batch 32, "
-                  "4 of 8 experts per layer in pinned host memory)",
+        "metric": f"streamed MoE stack decode tokens/sec ({NL}-layer Mixtral-shaped stack, batch {T}, "
+                  "half of the experts in pinned host memory)",
         "value": tokens / t_wall, "unit": "tokens/s", "n_gpus": 1, "steps": NS, "warmup": 0,
         "ms_per_step": t_wall / NS * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"c5_stack: {NL} layers x {NS} decode steps, T={T}, weights repeat "
                                f"with period {P} layers, 2 on-demand + 2x2 prefetch slots, "
-                               f"{args.layout} weight layout"},
+                               f"{args.layout} weight layout, prefetch policy {args.c5_policy}, "
+                               f"{args.c5_residency} residency"},
+        "prefetch": {"policy": args.c5_policy, "issued": agg["n_prefetch_issued"], "hits": agg["n_hit"],
+                     "wasted": agg["n_wasted"], "misses": agg["n_miss"],
+                     "hit_rate_of_issued": agg["n_hit"] / agg["n_prefetch_issued"]
+                     if agg["n_prefetch_issued"] else None,
+                     "presched": {"t_io_ms": costs.t_io * 1e3, "t_g_ms": costs.t_g * 1e3,
+                                  "t_attn_ms": costs.t_attn * 1e3, **sched_log}
+                     if args.c5_policy == "presched" else None},
+        "hot_table": hot_info,
         "overlap": {
             "T_c_s": t_c, "T_x_s": t_x, "T_wall_s": t_wall, "T_wall_sync_s": t_sync,
             "hidden_literal_A": 1.0 - (t_wall - t_c) / t_x if t_x > 0 else None,

@@ -1,4 +1,5 @@
-"""ctypes binding of include/moe_hotpath.h -- argument marshalling only.
+"""ctypes binding of include/moe_hotpath.h and include/moe_sched.h -- argument
+marshalling only.
 
 Names mirror the C entry points.  Tensors are torch CUDA tensors owned by the
 caller; bf16 data may be passed as ``torch.bfloat16`` or as raw ``int16`` /
@@ -64,6 +65,31 @@ class moe_phase_times(C.Structure):
                 ("gate_up_only_ms", C.c_double), ("gate_up_only_layers", C.c_int64)]
 
 
+SCHED_MAX = 128
+
+
+class moe_presched_costs(C.Structure):
+    _fields_ = [("t_io", C.c_double), ("t_g", C.c_double), ("t_attn", C.c_double),
+                ("beta", C.c_double), ("C", C.c_double), ("alpha", C.c_double),
+                ("r_hit", C.c_double), ("cpu_executor", C.c_int32)]
+
+
+class moe_pending(C.Structure):
+    _fields_ = [("expert", C.c_int32), ("tokens", C.c_int32)]
+
+
+class moe_presched_plan(C.Structure):
+    _fields_ = [("n_cur", C.c_int32), ("n_next", C.c_int32),
+                ("cur_sorted", C.c_int32 * SCHED_MAX), ("next_sorted", C.c_int32 * SCHED_MAX),
+                ("n_all", C.c_int32), ("all_layer", C.c_int32 * (2 * SCHED_MAX)),
+                ("all_expert", C.c_int32 * (2 * SCHED_MAX)),
+                ("all_in_queue", C.c_int32 * (2 * SCHED_MAX)),
+                ("i_prime", C.c_int32), ("n_ondemand", C.c_int32),
+                ("ondemand", C.c_int32 * SCHED_MAX),
+                ("T_gap", C.c_double), ("f", C.c_double), ("f_abs", C.c_int32), ("xi", C.c_double),
+                ("n_prefetch", C.c_int32), ("prefetch", C.c_int32 * SCHED_MAX)]
+
+
 if not os.path.exists(LIB):
     raise ImportError(
         f"{LIB} is missing: build it first (python -m paper_2509_23638_amd.build, or "
@@ -95,7 +121,13 @@ _lib.moe_set_option.argtypes = [_P, C.c_int32, C.c_int64]
 _lib.moe_pack_weights.argtypes = [_P, _P, C.c_int32, C.c_int32, _P]
 _lib.moe_rmsnorm.argtypes = [_SH, _P, _P, C.c_float, _P]
 _lib.moe_workspace_views.argtypes = [_SH, _P] + [C.POINTER(_P)] * 7
-for _n in ("moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_create",
+_lib.moe_counter_add.argtypes = [_SH, _P, _P, _P]
+_lib.moe_hot_table.argtypes = [_P, C.c_int32, C.c_int32, C.c_int64, _P]
+_lib.moe_predict_counts.argtypes = [_SH, _P, _P, _P, _P, _P, _P]
+_lib.moe_presched.argtypes = [C.POINTER(moe_presched_costs), C.POINTER(moe_pending), C.c_int32,
+                              C.POINTER(moe_pending), C.c_int32, C.POINTER(moe_presched_plan)]
+for _n in ("moe_counter_add", "moe_hot_table", "moe_predict_counts", "moe_presched",
+           "moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_create",
            "moe_destroy", "moe_layer_forward", "moe_stream_totals_get", "moe_workspace_views",
            "moe_phase_timing", "moe_phase_times_get", "moe_probe_copy", "moe_probe_read",
            "moe_rmsnorm", "moe_set_option", "moe_pack_weights"):
@@ -105,7 +137,8 @@ EXPORTS = ["moe_version", "moe_last_error", "moe_workspace_bytes", "moe_route", 
            "moe_grouped_ffn", "moe_combine", "moe_create", "moe_destroy", "moe_layer_forward",
            "moe_stream_totals_get", "moe_workspace_views", "moe_phase_timing",
            "moe_phase_times_get", "moe_probe_copy", "moe_probe_read", "moe_rmsnorm",
-           "moe_set_option", "moe_pack_weights"]
+           "moe_set_option", "moe_pack_weights",
+           "moe_counter_add", "moe_hot_table", "moe_predict_counts", "moe_presched"]
 
 
 def _check(st: int):
@@ -388,3 +421,44 @@ def moe_workspace_views(shape, workspace: torch.Tensor) -> dict:
         nbytes = n * torch.empty((), dtype=dt).element_size()
         out[name] = workspace[off:off + nbytes].view(dt).view(shp)
     return out
+
+
+# ------------------------------------------------------------ moe_sched.h --
+def moe_counter_add(shape, count: torch.Tensor, total: torch.Tensor, stream=None):
+    _check(_lib.moe_counter_add(C.byref(shape), _ptr(count, "count", (torch.int32,), shape.E),
+                                _ptr(total, "total", (torch.int64,), shape.E), _stream(stream)))
+
+
+def moe_hot_table(tokens, budget_experts: int):
+    """tokens: int64 array-like [L, E] on the host -> bool numpy array [L, E]."""
+    import numpy as np
+    t = np.ascontiguousarray(np.asarray(tokens, dtype=np.int64))
+    if t.ndim != 2:
+        raise ValueError("tokens must be [L, E]")
+    L, E = t.shape
+    out = np.zeros((L, E), dtype=np.uint8)
+    _check(_lib.moe_hot_table(t.ctypes.data, L, E, int(budget_experts), out.ctypes.data))
+    return out.astype(bool)
+
+
+def moe_predict_counts(shape, X, Wr_next, bias_next, pred_count, workspace, stream=None):
+    sd = _storage_dtypes(shape)
+    _check(_lib.moe_predict_counts(
+        C.byref(shape), _ptr(X, "X", sd, shape.T * shape.H),
+        _ptr(Wr_next, "Wr_next", sd, shape.E * shape.H),
+        _ptr(bias_next, "bias_next", (torch.float32,), shape.E),
+        _ptr(pred_count, "pred_count", (torch.int32,), shape.E),
+        _ptr(workspace, "workspace"), _stream(stream)))
+
+
+def moe_presched(costs: moe_presched_costs, cur, nxt) -> moe_presched_plan:
+    """cur / nxt: sequences of (expert id, pending tokens)."""
+    def pack(lst):
+        arr = (moe_pending * max(1, len(lst)))()
+        for i, (e, m) in enumerate(lst):
+            arr[i].expert, arr[i].tokens = int(e), int(m)
+        return arr
+    plan = moe_presched_plan()
+    _check(_lib.moe_presched(C.byref(costs), pack(cur), len(cur), pack(nxt), len(nxt),
+                             C.byref(plan)))
+    return plan

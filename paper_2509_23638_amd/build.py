@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoe_hotpath.so")
 SOURCES = ["common.hip", "route.hip", "permute.hip", "ffn.hip", "combine.hip", "layer.hip",
-           "probe.hip", "stack.hip", "pack.hip"]
+           "probe.hip", "stack.hip", "pack.hip", "sched.hip"]
 FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
     "-Wall", "-Wno-unused-function",

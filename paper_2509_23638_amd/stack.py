@@ -82,6 +82,10 @@ class StreamedStack:
                 shape, self._router[p][0], self._router[p][1],
                 dev=(d["Wg"], d["Wu"], d["Wd"]), pinned=(h["Wg"], h["Wu"], h["Wd"]), layer_id=l))
         self._norm = None
+        self._pred = torch.zeros(E, dtype=torch.int32, device="cuda")
+        self._cur = torch.zeros(E, dtype=torch.int32, device="cuda")
+        self._in_slot = [set() for _ in range(self.n_layers)]   # experts prefetched for layer l
+        self.sched_log = {"n_decisions": 0, "n_prefetch_planned": 0, "f_sum": 0.0}
 
     def close(self):
         self.ctx.close()
@@ -114,6 +118,65 @@ class StreamedStack:
             stats.append(self.layer_forward(l, self._norm, out, residual=x, prefetch_next_mask=pm,
                                             next_l=nxt if pm is not None else None,
                                             want_stats=want_stats))
+            x = out
+        return x, stats
+
+
+    # ---- online prefetch policies (Section 3.2 predictor + Section 4.3 scheduler) ----
+    def predicted_counts(self, l_router: int, x_norm: torch.Tensor, into: torch.Tensor) -> np.ndarray:
+        """Tokens per expert when ``x_norm`` is routed by layer ``l_router``'s
+        gate (device work in the library; the E counts come back to the host)."""
+        Wr, b = self.layers[l_router].keep[0], self.layers[l_router].keep[1]
+        B.moe_predict_counts(self.shape, x_norm, Wr, b, into, self.ws)
+        return into.cpu().numpy()
+
+    def step_online(self, X: torch.Tensor, policy: str, costs: Optional[B.moe_presched_costs] = None,
+                    n_prefetch: int = 2, wrap_prefetch: bool = False):
+        """One pass with the prefetch set decided online, layer by layer:
+
+        ``gate_topn``  -- the ``n_prefetch`` non-resident experts of the next
+                          layer with the most predicted tokens (gate-based
+                          prediction from this layer's input);
+        ``presched``   -- the same prediction fed to PreSched together with this
+                          layer's own pending experts; the plan's prefetch list
+                          (cut to the slots available) is issued;
+        ``none``       -- on-demand loads only.
+        Returns (x_final, list of per-layer stats)."""
+        E = self.shape.E
+        if self._norm is None or self._norm.shape != X.shape:
+            self._norm = torch.empty_like(X)
+            self._bufs = [torch.empty_like(X), torch.empty_like(X)]
+        x = X
+        stats = []
+        for l in range(self.n_layers):
+            B.moe_rmsnorm(self.shape, x, self._norm)
+            out = self._bufs[l & 1]
+            nxt = l + 1 if l + 1 < self.n_layers else (0 if wrap_prefetch else None)
+            pm = None
+            if nxt is not None and policy != "none":
+                pred = self.predicted_counts(nxt, self._norm, self._pred)
+                cand = [(e, int(pred[e])) for e in range(E)
+                        if pred[e] > 0 and not self.resident[nxt][e]]
+                if policy == "gate_topn":
+                    chosen = [e for e, _ in sorted(cand, key=lambda r: (-r[1], r[0]))[:n_prefetch]]
+                elif policy == "presched":
+                    mine = self.predicted_counts(l, self._norm, self._cur)
+                    cur = [(e, int(mine[e])) for e in range(E)
+                           if mine[e] > 0 and not self.resident[l][e] and e not in self._in_slot[l]]
+                    plan = B.moe_presched(costs, cur, cand)
+                    chosen = list(plan.prefetch[:min(plan.n_prefetch, n_prefetch)])
+                    self.sched_log["n_decisions"] += 1
+                    self.sched_log["n_prefetch_planned"] += plan.n_prefetch
+                    self.sched_log["f_sum"] += plan.f
+                else:
+                    raise ValueError(policy)
+                pm = np.zeros(E, dtype=bool)
+                pm[chosen] = True
+                self._in_slot[nxt] = set(chosen)
+            st = self.layer_forward(l, self._norm, out, residual=x, prefetch_next_mask=pm,
+                                    next_l=nxt if pm is not None else None)
+            self._in_slot[l] = set()
+            stats.append(st)
             x = out
         return x, stats
 

@@ -1,5 +1,5 @@
 """The C-ABI library loads without a GPU and exports every function that
-include/moe_hotpath.h declares (no compute calls here)."""
+include/*.h declares (no compute calls here)."""
 import ctypes
 import os
 import re
@@ -7,14 +7,15 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "moe_hotpath.h")
+HEADERS = [os.path.join(ROOT, "include", h) for h in ("moe_hotpath.h", "moe_sched.h")]
 
 
 def _declared():
-    src = open(HEADER).read()
-    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    names = re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", src)
-    return sorted(set(names))
+    names = set()
+    for h in HEADERS:
+        src = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        names.update(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", src))
+    return sorted(names)
 
 
 @pytest.fixture(scope="module")
