@@ -115,10 +115,13 @@ size_t moe_workspace_bytes(const moe_shape* shape);
  *   X [T,H], Wr [E,H]  storage dtype;  bias [E] float32 or NULL (= zeros)
  *   topk_idx [T,k] int32, topk_w [T,k] float32          (outputs)
  *   logits_out [T,E] float64 or NULL                      (optional output)
- * T == 0 is legal and does nothing. */
+ *   workspace  moe_workspace_bytes(shape) bytes; may be NULL when logits_out
+ *              is given (the logits need a home between the two kernels)
+ * T == 0 is legal and does nothing.  MOE_ERR_WORKSPACE when both logits_out
+ * and workspace are NULL. */
 moe_status moe_route(const moe_shape* shape, const void* X, const void* Wr,
                      const float* bias, int32_t* topk_idx, float* topk_w,
-                     double* logits_out, void* stream);
+                     double* logits_out, void* workspace, void* stream);
 
 /* ---- a3: bucket the assignments by expert --------------------------------
  * The per-expert pending-token counts of Section 4.3.2 (Premise 1) plus the

@@ -102,7 +102,7 @@ _lib.moe_version.restype = C.c_char_p
 _lib.moe_last_error.restype = C.c_char_p
 _lib.moe_workspace_bytes.restype = C.c_size_t
 _lib.moe_workspace_bytes.argtypes = [_SH]
-_lib.moe_route.argtypes = [_SH, _P, _P, _P, _P, _P, _P, _P]
+_lib.moe_route.argtypes = [_SH, _P, _P, _P, _P, _P, _P, _P, _P]
 _lib.moe_permute.argtypes = [_SH, _P, _P, _P, _P, _P, _P]
 _lib.moe_grouped_ffn.argtypes = [_SH, _P, _P, _P, C.POINTER(moe_expert_ptrs),
                                  C.POINTER(C.c_uint64), _P, _P, _P]
@@ -219,14 +219,15 @@ def alloc_workspace(shape: moe_shape, device="cuda") -> torch.Tensor:
     return torch.empty(moe_workspace_bytes(shape), dtype=torch.uint8, device=device)
 
 
-def moe_route(shape, X, Wr, bias, topk_idx, topk_w, logits_out=None, stream=None):
+def moe_route(shape, X, Wr, bias, topk_idx, topk_w, logits_out=None, workspace=None, stream=None):
     sd = _storage_dtypes(shape)
     A = shape.T * shape.k
     _check(_lib.moe_route(
         C.byref(shape), _ptr(X, "X", sd, shape.T * shape.H), _ptr(Wr, "Wr", sd, shape.E * shape.H),
         _ptr(bias, "bias", (torch.float32,), shape.E),
         _ptr(topk_idx, "topk_idx", (torch.int32,), A), _ptr(topk_w, "topk_w", (torch.float32,), A),
-        _ptr(logits_out, "logits_out", (torch.float64,), shape.T * shape.E), _stream(stream)))
+        _ptr(logits_out, "logits_out", (torch.float64,), shape.T * shape.E),
+        _ptr(workspace, "workspace"), _stream(stream)))
 
 
 def moe_permute(shape, topk_idx, count, offset, perm, inv_perm, stream=None):

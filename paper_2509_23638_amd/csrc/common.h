@@ -38,7 +38,7 @@ static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 
 // Workspace carve-up (all offsets 256-byte aligned).
 struct WorkspaceLayout {
-  size_t topk_idx, topk_w, count, offset, perm, inv_perm, plan, h, y, total;
+  size_t topk_idx, topk_w, count, offset, perm, inv_perm, plan, logits, h, y, total;
 };
 WorkspaceLayout workspace_layout(const moe_shape& s);
 

@@ -56,6 +56,7 @@ WorkspaceLayout workspace_layout(const moe_shape& s) {
   L.perm = take(A * 4);
   L.inv_perm = take(A * 4);
   L.plan = take(plan_bytes(s));
+  L.logits = take((size_t)s.T * s.E * sizeof(double));
   L.h = take(rows * s.F * elem_size(s));
   L.y = take(rows * s.H * 4);
   L.total = o;

@@ -370,7 +370,8 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
   } while (0)
   if (timed) c->phase_kinds.push_back(timed);
   PHASE_MARK(0);
-  st = launch_route(s, X, layer->Wr, layer->bias, topk_idx, topk_w, nullptr, stream);
+  st = launch_route(s, X, layer->Wr, layer->bias, topk_idx, topk_w,
+                    reinterpret_cast<double*>(w + L.logits), stream);
   if (st != MOE_OK) return st;
   PHASE_MARK(1);
   st = launch_permute(s, topk_idx, count, offset, perm, inv_perm, stream);

@@ -1,16 +1,24 @@
 // Gate of the MoE block (paper Section 2.1, "e_i, w_i = Gate(a)"): router GEMM
-// with float64 accumulation, k rounds of wave-level arg-max with lowest-index
-// tie-break, softmax weights renormalised over the selected experts.
+// with float64 accumulation, selection of the k largest logits with
+// lowest-index tie-break, softmax weights renormalised over the selected
+// experts.
 //
-// Work split: one workgroup of NW wavefronts handles TPB tokens.  Wave w owns
-// the experts e with e % NW == w; every lane covers 8 consecutive hidden
-// positions per step, so X and Wr are read with 16-byte (bf16) coalesced loads,
-// several steps' loads in flight at once.  Per-lane partial sums are folded to
-// one value per 16-lane row with DPP moves, the four row partials meet in LDS,
-// and wave tk then selects for token tk by rank: lane e counts the experts
-// that beat expert e (two candidates per lane when E > 64) -- no cross-lane
-// traffic at all in the selection.
+// Logits, three forms chosen by shape:
+//  * few experts (E <= 8): one workgroup per token, 8 waves x 64 lanes split
+//    the hidden dimension, and the same launch selects;
+//  * few tokens, many experts: blocks of (4 or 16) tokens x 4 experts, so that
+//    every workgroup reads only its rows of Wr and the router matrix is spread
+//    over the chip instead of being pulled whole into every compute unit;
+//    inside a wave the four 16-lane rows hold four token sets and a row's 16
+//    lanes split the hidden dimension (256 contiguous bytes per row and fetch);
+//  * many tokens: 16 x 16 tiles on the float64 matrix cores.
+// Per-lane partial sums fold with DPP moves, waves' partials meet in LDS, all
+// in a fixed order.  Selection: one wavefront per token, k rounds of arg-max
+// over 64-bit sortable keys, reducing only the keys' high words unless lanes
+// tie on them.
 #include "common.h"
+
+#include <stdlib.h>
 
 namespace moe {
 namespace {
@@ -76,175 +84,412 @@ __device__ __forceinline__ double row16_sum(double v) {
   return v;
 }
 
-// Rank of candidate c (expert index e) among the E logits of one token: the
-// number of experts that beat it, where o beats e if its logit is larger, or
-// equal with a lower index -- the order k rounds of arg-max with lowest-index
-// ties produce.  The logits are read from LDS eight at a time so that the
-// reads overlap instead of costing one LDS round trip each.
-__device__ __forceinline__ void ranks_of(const double* logit, int E, double c0, int e0, double c1,
-                                         int e1, int& r0, int& r1) {
-  r0 = 0;
-  r1 = 0;
-  for (int ob = 0; ob < E; ob += 8) {
-    double v[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = logit[min(ob + u, E - 1)];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int o = ob + u;
-      const bool in = o < E;
-      r0 += (in && (v[u] > c0 || (v[u] == c0 && o < e0))) ? 1 : 0;
-      r1 += (in && (v[u] > c1 || (v[u] == c1 && o < e1))) ? 1 : 0;
+// Order-preserving map of a finite float64 to an unsigned key: larger value,
+// larger key; -0.0 and +0.0 share a key (the +0.0 folds the sign of zero) so
+// that they tie like the float64 comparison says.  Every real key is above 0,
+// which marks "no candidate".
+__device__ __forceinline__ uint64_t sortable_key(double v) {
+  const uint64_t u = (uint64_t)__double_as_longlong(v + 0.0);
+  return (u >> 63) ? ~u : (u | 0x8000000000000000ull);
+}
+
+// Maximum over the wavefront, returned uniform: xor-1 / xor-2 inside quads,
+// mirrored half-row and row (every lane of a 16-lane row then holds the row
+// maximum), then the four rows' values are read out and combined as scalars.
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, false));
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, false));
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, false));
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, false));
+  const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)v, 0);
+  const uint32_t b = (uint32_t)__builtin_amdgcn_readlane((int)v, 16);
+  const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)v, 32);
+  const uint32_t d = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+  return max(max(a, b), max(c, d));
+}
+
+__device__ __forceinline__ double readlane_f64(double v, int lane_uniform) {
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), lane_uniform);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane_uniform);
+  return __hiloint2double(hi, lo);
+}
+
+// Selection for one token by one wavefront: k rounds of arg-max with the
+// lowest index winning ties (exactly the reference's selection), then the
+// renormalised softmax weights.  Lane l offers experts l (logit c0) and l + 64
+// (c1) as 64-bit sortable keys, the better of the two per round.  A round
+// reduces only the keys' high words over the wave (32-bit maximum through DPP);
+// the low words, and then the expert indices, are consulted only when several
+// lanes share the leading word -- a wave-uniform, rarely taken branch.  The
+// r-th winner's logit and index are parked in lane r, so the weights need one
+// expf per lane and no LDS.  Every lane of the wave must call this.
+__device__ __forceinline__ void select_topk(double c0, double c1, int E, int k, bool store, size_t t,
+                                            int lane, int32_t* __restrict__ topk_idx,
+                                            float* __restrict__ topk_w) {
+  const int e0 = lane, e1 = lane + MOE_WAVE;
+  uint64_t key0 = e0 < E ? sortable_key(c0) : 0ull;
+  uint64_t key1 = e1 < E ? sortable_key(c1) : 0ull;
+  double sel_v = 0.0;
+  int32_t sel_i = 0;
+  for (int r = 0; r < k; ++r) {
+    const bool first = key0 >= key1;                   // equal keys: the lower index
+    const uint64_t best = first ? key0 : key1;
+    const uint32_t hi = (uint32_t)(best >> 32), lo = (uint32_t)best;
+    const uint32_t idx = first ? e0 : e1;
+    const uint32_t top = wave_max_u32(hi);
+    uint64_t m = __builtin_amdgcn_ballot_w64(hi == top);
+    if (__popcll(m) > 1) {
+      const bool in = hi == top;
+      const uint32_t top_lo = wave_max_u32(in ? lo : 0u);
+      m = __builtin_amdgcn_ballot_w64(in && lo == top_lo);
+      if (__popcll(m) > 1) {
+        const bool in2 = in && lo == top_lo;
+        const uint32_t low_idx = wave_max_u32(in2 ? ~idx : 0u);   // largest ~idx = smallest index
+        m = __builtin_amdgcn_ballot_w64(in2 && ~idx == low_idx);
+      }
     }
+    const int winner = __ffsll((unsigned long long)m) - 1;       // uniform; m is never empty
+    const double wv = readlane_f64(first ? c0 : c1, winner);
+    const int32_t wi = __builtin_amdgcn_readlane((int)idx, winner);
+    if (lane == r) { sel_v = wv; sel_i = wi; }
+    if (lane == winner) { if (first) key0 = 0ull; else key1 = 0ull; }
+  }
+  // softmax over all experts renormalised over the selected ones equals a
+  // softmax over the selected logits; the largest one (lane 0's) is the shift.
+  // k <= 16: the selected values sit in the first 16-lane row.
+  const double top_v = readlane_f64(sel_v, 0);
+  float ex = lane < k ? expf((float)(sel_v - top_v)) : 0.f;
+  float sum = ex;
+  sum += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(sum), 0xB1, 0xF, 0xF, false));
+  sum += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(sum), 0x4E, 0xF, 0xF, false));
+  sum += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(sum), 0x141, 0xF, 0xF, false));
+  sum += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(sum), 0x140, 0xF, 0xF, false));
+  if (store && lane < k) {
+    topk_idx[t * k + lane] = sel_i;
+    topk_w[t * k + lane] = ex / sum;
   }
 }
 
-// NW  = wavefronts per workgroup; wave w owns the experts e with e % NW == w
-// TPB = tokens per workgroup (they share every router-weight fetch)
-// EPW = compile-time bound on experts per wave (keeps accumulators in VGPRs)
-// UNR = hidden-dimension steps (512 positions each) whose fetches are issued together
-template <typename ST, int NW, int TPB, int EPW, int UNR>
-__global__ __launch_bounds__(NW* MOE_WAVE) void route_kernel(
+// One 128-position step of a wave: raw fetches of TPL token rows and EPW
+// router rows (8 positions per lane).  Rows past the batch or the expert list
+// re-read the last valid row (their sums are never stored); lanes past H
+// re-read column 0 and contribute zeros.
+template <typename ST, int EPW, int TPL> struct RouteStep {
+  typename Load8<ST>::Raw x[TPL], w[EPW];
+  bool live;
+  __device__ __forceinline__ void load(const void* X, const void* Wr, int tl, int e0, int T, int E,
+                                       int H, int hc) {
+    live = hc < H;
+    const size_t at = live ? hc : 0;
+#pragma unroll
+    for (int j = 0; j < TPL; ++j) x[j] = Load8<ST>::fetch(X, (size_t)min(tl + j, T - 1) * H + at);
+#pragma unroll
+    for (int i = 0; i < EPW; ++i) w[i] = Load8<ST>::fetch(Wr, (size_t)min(e0 + i, E - 1) * H + at);
+  }
+  __device__ __forceinline__ void mac(double (&acc)[EPW][TPL]) const {
+    double xv[TPL][8];
+#pragma unroll
+    for (int j = 0; j < TPL; ++j) {
+      Load8<ST>::widen(x[j], xv[j]);
+      if (!live)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) xv[j][q] = 0.0;
+    }
+#pragma unroll
+    for (int i = 0; i < EPW; ++i) {
+      double wv[8];
+      Load8<ST>::widen(w[i], wv);
+#pragma unroll
+      for (int j = 0; j < TPL; ++j)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc[i][j] = fma(xv[j][q], wv[q], acc[i][j]);
+    }
+  }
+};
+
+// Logits of a block of tokens x experts.
+// EPW  = experts per workgroup, TPL = tokens per lane.
+// RT   = 4: the four 16-lane rows of a wave hold four token sets (a wave covers
+//           4*TPL tokens) and a row's 16 lanes split the hidden dimension, 128
+//           positions per step;
+//        1: all 64 lanes split the hidden dimension, 512 positions per step
+//           (a wave covers TPL tokens) -- more lanes per token, for batches too
+//           small to fill the chip otherwise.
+// KS   = wavefronts that split the hidden dimension (steps round robin).
+// UNR  = steps whose fetches are issued together.  PIPE: instead, the next
+//        step's fetches are issued before the current step is multiplied (long
+//        per-wave loops of the many-token case).
+// FUSE = the workgroup holds all E <= EPW logits of its tokens, so it also
+//        selects (wave j for token j): one launch for the whole gate.
+template <typename ST, int EPW, int TPL, int RT, int KS, int UNR, bool PIPE, bool FUSE>
+__global__ __launch_bounds__(KS* MOE_WAVE) void route_logits_kernel(
     const void* __restrict__ X, const void* __restrict__ Wr, const float* __restrict__ bias,
-    int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, double* __restrict__ logits_out,
-    int T, int H, int E, int k) {
-  __shared__ double s_row[TPB][MOE_MAX_E][4];   // one partial per 16-lane row
-  __shared__ double s_logit[TPB][MOE_MAX_E];
-  __shared__ double s_sel[TPB][MOE_MAX_K];
+    double* __restrict__ logits, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, int T,
+    int H, int E, int k) {
+  constexpr int TPW = RT * TPL;                      // tokens per workgroup
+  constexpr int NP = KS * (4 / RT);                  // partial sums per (expert, token)
+  constexpr int PS = RT == 4 ? 128 : 512;            // positions per step
+  static_assert(!FUSE || TPW <= KS, "one selecting wave per token");
+  __shared__ double s_part[NP][EPW][TPW];
+  __shared__ double s_logit[FUSE ? TPW : 1][FUSE ? EPW : 1];
 
   const int lane = threadIdx.x & (MOE_WAVE - 1);
   const int wave = threadIdx.x / MOE_WAVE;
-  const int t0 = blockIdx.x * TPB;
+  const int row = lane >> 4, col = lane & 15;
+  const int t0 = blockIdx.x * TPW, e0 = blockIdx.y * EPW;
+  const int tl = t0 + (RT == 4 ? row * TPL : 0);     // this lane's first token
+  const int hl = (RT == 4 ? col : lane) * 8;         // this lane's offset inside a step
+  constexpr int stride = KS * PS;                    // between a wave's steps
 
-  double acc[EPW][TPB];
+  double acc[EPW][TPL];
 #pragma unroll
   for (int i = 0; i < EPW; ++i)
 #pragma unroll
-    for (int j = 0; j < TPB; ++j) acc[i][j] = 0.0;
+    for (int j = 0; j < TPL; ++j) acc[i][j] = 0.0;
 
-  for (int base = 0; base < H; base += UNR * MOE_WAVE * 8) {
-    // Every fetch of this step is issued before anything is used (raw form:
-    // 4 registers per 8 bf16 values), so the step costs one round trip to
-    // memory.  No branch on the expert index: a wave's slots past E re-read
-    // the last expert's row and accumulate a value nobody stores, which keeps
-    // the body straight-line.
-    typename Load8<ST>::Raw xraw[UNR][TPB], wraw[UNR][EPW];
-    bool live[UNR];
+  typedef RouteStep<ST, EPW, TPL> Step;
+  if constexpr (!PIPE) {
+    for (int base = wave * PS; base < H; base += UNR * stride) {
+      Step st[UNR];
 #pragma unroll
-    for (int u = 0; u < UNR; ++u) {
-      const int hc = base + u * MOE_WAVE * 8 + lane * 8;
-      live[u] = hc < H;
-      const size_t at = live[u] ? hc : 0;   // dead lanes re-read column 0 and are zeroed below
+      for (int u = 0; u < UNR; ++u) st[u].load(X, Wr, tl, e0, T, E, H, base + u * stride + hl);
 #pragma unroll
-      for (int j = 0; j < TPB; ++j)
-        xraw[u][j] = Load8<ST>::fetch(X, (size_t)min(t0 + j, T - 1) * H + at);
-#pragma unroll
-      for (int i = 0; i < EPW; ++i)
-        wraw[u][i] = Load8<ST>::fetch(Wr, (size_t)min(wave + i * NW, E - 1) * H + at);
+      for (int u = 0; u < UNR; ++u) st[u].mac(acc);
     }
-#pragma unroll
-    for (int u = 0; u < UNR; ++u) {
-      double xv[TPB][8];
-#pragma unroll
-      for (int j = 0; j < TPB; ++j) {
-        Load8<ST>::widen(xraw[u][j], xv[j]);
-        if (!live[u])
-#pragma unroll
-          for (int q = 0; q < 8; ++q) xv[j][q] = 0.0;
-      }
-#pragma unroll
-      for (int i = 0; i < EPW; ++i) {
-        double wv[8];
-        Load8<ST>::widen(wraw[u][i], wv);
-#pragma unroll
-        for (int j = 0; j < TPB; ++j)
-#pragma unroll
-          for (int q = 0; q < 8; ++q) acc[i][j] = fma(xv[j][q], wv[q], acc[i][j]);
-      }
+  } else {
+    Step a, b;
+    int base = wave * PS;
+    if (base < H) a.load(X, Wr, tl, e0, T, E, H, base + hl);
+    while (base < H) {
+      if (base + stride < H) b.load(X, Wr, tl, e0, T, E, H, base + stride + hl);
+      a.mac(acc);
+      base += stride;
+      if (base >= H) break;
+      if (base + stride < H) a.load(X, Wr, tl, e0, T, E, H, base + stride + hl);
+      b.mac(acc);
+      base += stride;
     }
   }
 
-  // lane partials -> one partial per 16-lane row -> LDS
 #pragma unroll
-  for (int i = 0; i < EPW; ++i) {
-    const int e = wave + i * NW;
-    if (e < E) {
+  for (int i = 0; i < EPW; ++i)
 #pragma unroll
-      for (int j = 0; j < TPB; ++j) {
-        const double r = row16_sum(acc[i][j]);
-        if ((lane & 15) == 0) s_row[j][e][lane >> 4] = r;
+    for (int j = 0; j < TPL; ++j) {
+      const double r = row16_sum(acc[i][j]);
+      if (col == 0) {
+        if (RT == 4) s_part[wave][i][row * TPL + j] = r;
+        else s_part[wave * 4 + row][i][j] = r;
       }
     }
-  }
   __syncthreads();
-  for (int i = threadIdx.x; i < TPB * E; i += NW * MOE_WAVE) {
-    const int j = TPB == 1 ? 0 : i / E, e = i - j * E;
-    const double b = bias ? (double)bias[e] : 0.0;
-    const double v = ((s_row[j][e][0] + s_row[j][e][1]) + (s_row[j][e][2] + s_row[j][e][3])) + b;
-    s_logit[j][e] = v;
-    if (logits_out && t0 + j < T) logits_out[(size_t)(t0 + j) * E + e] = v;
+  for (int p = threadIdx.x; p < EPW * TPW; p += KS * MOE_WAVE) {
+    const int i = p / TPW, j = p - i * TPW;
+    const int e = e0 + i, t = t0 + j;
+    double v = s_part[0][i][j];
+#pragma unroll
+    for (int w = 1; w < NP; ++w) v += s_part[w][i][j];
+    v += (bias && e < E) ? (double)bias[e] : 0.0;
+    if (e < E && t < T) logits[(size_t)t * E + e] = v;
+    if (FUSE) s_logit[j][i] = v;
   }
-  __syncthreads();
-
-  // wave tk selects for token t0 + tk: lane e ranks expert e (and e + 64)
-  const int tk = wave;
-  const bool mine = tk < TPB && t0 + tk < T;
-  if (mine) {
-    const double ninf = -__builtin_huge_val();
-    const int e0 = lane, e1 = lane + MOE_WAVE;
-    const double c0 = e0 < E ? s_logit[tk][e0] : ninf;
-    const double c1 = e1 < E ? s_logit[tk][e1] : ninf;
-    int r0, r1;
-    ranks_of(s_logit[tk], E, c0, e0, c1, e1, r0, r1);
-    const size_t t = (size_t)(t0 + tk);
-    if (e0 < E && r0 < k) { s_sel[tk][r0] = c0; topk_idx[t * k + r0] = e0; }
-    if (e1 < E && r1 < k) { s_sel[tk][r1] = c1; topk_idx[t * k + r1] = e1; }
-  }
-  __syncthreads();
-  if (mine && lane < k) {
-    // softmax over all experts renormalised over the selected ones equals a
-    // softmax over the selected logits; the largest one is the shift
-    const double first = s_sel[tk][0];
-    float denom = 0.f;
-    for (int j = 0; j < k; ++j) denom += expf((float)(s_sel[tk][j] - first));
-    topk_w[(size_t)(t0 + tk) * k + lane] = expf((float)(s_sel[tk][lane] - first)) / denom;
+  if constexpr (FUSE) {
+    __syncthreads();
+    if (wave < TPW) {                                // whole wavefronts; no barrier below
+      const bool store = t0 + wave < T;
+      const double c0 = lane < EPW ? s_logit[wave][lane] : 0.0;
+      select_topk(c0, 0.0, E, k, store, (size_t)min(t0 + wave, T - 1), lane, topk_idx, topk_w);
+    }
   }
 }
 
-template <typename ST>
-void launch_typed(const moe_shape& s, const void* X, const void* Wr, const float* bias,
-                  int32_t* topk_idx, float* topk_w, double* logits_out, hipStream_t stream) {
-#define ROUTE_LAUNCH(NW, TPB, EPW, UNR)                                                        \
-  hipLaunchKernelGGL((route_kernel<ST, NW, TPB, EPW, UNR>), dim3((s.T + TPB - 1) / TPB),       \
-                     dim3(NW * MOE_WAVE), 0, stream, X, Wr, bias, topk_idx, topk_w, logits_out, \
-                     s.T, s.H, s.E, s.k)
-  // float32 rows take twice the registers per fetch: half the steps in flight
-  constexpr int W = sizeof(ST) == 2 ? 2 : 1;
-  if (s.T >= 512 && s.E <= 64) {
-    // many tokens: throughput matters; two tokens share each router-weight fetch
-    if (s.E <= 8) ROUTE_LAUNCH(4, 2, 2, 2 * W);
-    else if (s.E <= 32) ROUTE_LAUNCH(4, 2, 8, W);
-    else ROUTE_LAUNCH(4, 2, 16, 1);
-  } else {
-    // few tokens: latency matters; eight waves per token, as much of the
-    // hidden dimension in flight per wave as the registers allow
-    if (s.E <= 8) ROUTE_LAUNCH(8, 1, 1, 4 * W);
-    else if (s.E <= 32) ROUTE_LAUNCH(8, 1, 4, 2 * W);
-    else if (s.E <= 64) ROUTE_LAUNCH(8, 1, 8, 2 * W);
-    else ROUTE_LAUNCH(8, 1, 16, W);
+// Logits on the float64 matrix cores: a wavefront owns a 16-token x 16-expert
+// tile and multiplies it with v_mfma_f64_16x16x4_f64 -- lane (r = l % 16,
+// g = l / 16) supplies X[token r][k] and Wr[expert r][k] for the four k of its
+// group g, and holds D[token 4i + g][expert r] in accumulator element i.  A
+// lane fetches 8 consecutive hidden positions at a time (one 16-byte load for
+// bf16), which feed 8 MFMAs; the k order inside a 32-position step is
+// permuted the same way for both operands, so the sums are unaffected.  Each
+// widened value is used by 16 multiply-adds instead of one, which is what
+// makes this the many-token form: the conversion work of the vector kernel
+// is gone and the float64 multiply-add rate is what is left.  KS waves split
+// the hidden dimension into contiguous runs and their partial tiles meet in
+// LDS; UNR steps are fetched together, one batch ahead of the batch being
+// multiplied.
+typedef double d4 __attribute__((ext_vector_type(4)));
+
+template <typename ST, int KS, int UNR>
+__global__ __launch_bounds__(KS* MOE_WAVE) void route_logits_mfma_kernel(
+    const void* __restrict__ X, const void* __restrict__ Wr, const float* __restrict__ bias,
+    double* __restrict__ logits, int T, int H, int E) {
+  typedef typename Load8<ST>::Raw Raw;
+  __shared__ double s_part[KS][16][17];
+  const int lane = threadIdx.x & (MOE_WAVE - 1);
+  const int wave = threadIdx.x / MOE_WAVE;
+  const int r = lane & 15, g = lane >> 4;
+  const int t0 = blockIdx.x * 16, e0 = blockIdx.y * 16;
+  const size_t xrow = (size_t)min(t0 + r, T - 1) * H;   // rows past the end re-read the last one
+  const size_t wrow = (size_t)min(e0 + r, E - 1) * H;
+
+  const int steps = (H + 31) / 32, per_wave = (steps + KS - 1) / KS;
+  const int k_end = min((wave + 1) * per_wave * 32, H);
+
+  d4 acc[4];                                            // independent chains
+#pragma unroll
+  for (int i = 0; i < 4; ++i) acc[i] = d4{0.0, 0.0, 0.0, 0.0};
+
+  struct Batch {
+    Raw xr[UNR], wr[UNR];
+    __device__ __forceinline__ void load(const void* X, const void* Wr, size_t xrow, size_t wrow,
+                                         int at0, int k_end) {
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        const int hc = at0 + u * 32;
+        const size_t at = hc < k_end ? hc : 0;          // past the run: a valid address, zeroed in mac
+        xr[u] = Load8<ST>::fetch(X, xrow + at);
+        wr[u] = Load8<ST>::fetch(Wr, wrow + at);
+      }
+    }
+    __device__ __forceinline__ void mac(d4 (&acc)[4], int at0, int k_end) const {
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        const bool live = at0 + u * 32 < k_end;
+        double xv[8], wv[8];
+        Load8<ST>::widen(xr[u], xv);
+        Load8<ST>::widen(wr[u], wv);
+        // a step past the run multiplies zeros: straight-line code schedules
+        // better than a branch around the MFMAs
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+          acc[q & 3] = __builtin_amdgcn_mfma_f64_16x16x4f64(live ? xv[q] : 0.0, wv[q], acc[q & 3], 0, 0, 0);
+      }
+    }
+  };
+  Batch a, b;
+  int base = wave * per_wave * 32;
+  constexpr int adv = UNR * 32;
+  if (base < k_end) a.load(X, Wr, xrow, wrow, base + g * 8, k_end);
+  while (base < k_end) {
+    if (base + adv < k_end) b.load(X, Wr, xrow, wrow, base + adv + g * 8, k_end);
+    a.mac(acc, base + g * 8, k_end);
+    base += adv;
+    if (base >= k_end) break;
+    if (base + adv < k_end) a.load(X, Wr, xrow, wrow, base + adv + g * 8, k_end);
+    b.mac(acc, base + g * 8, k_end);
+    base += adv;
   }
-#undef ROUTE_LAUNCH
+  const d4 sum = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) s_part[wave][4 * i + g][r] = sum[i];
+  __syncthreads();
+  for (int p = threadIdx.x; p < 256; p += KS * MOE_WAVE) {
+    const int j = p >> 4, i = p & 15;
+    const int t = t0 + j, e = e0 + i;
+    if (t < T && e < E) {
+      double v = s_part[0][j][i];
+#pragma unroll
+      for (int w = 1; w < KS; ++w) v += s_part[w][j][i];
+      logits[(size_t)t * E + e] = v + (bias ? (double)bias[e] : 0.0);
+    }
+  }
+}
+
+constexpr int kSelectWaves = 4;   // tokens per selection workgroup
+constexpr long kMfmaTiles = 128;   // 16 x 16 logit tiles from which the matrix-core form is used
+
+// Selection as a launch of its own (E larger than one logits block): one
+// wavefront per token.
+__global__ __launch_bounds__(kSelectWaves* MOE_WAVE) void route_select_kernel(
+    const double* __restrict__ logits, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+    int T, int E, int k) {
+  const int lane = threadIdx.x & (MOE_WAVE - 1);
+  const int tk = threadIdx.x / MOE_WAVE;
+  const int t = min(blockIdx.x * kSelectWaves + tk, T - 1);
+  const bool store = blockIdx.x * kSelectWaves + tk < T;
+  const int e0 = lane, e1 = lane + MOE_WAVE;
+  const double c0 = e0 < E ? logits[(size_t)t * E + e0] : 0.0;
+  const double c1 = e1 < E ? logits[(size_t)t * E + e1] : 0.0;
+  select_topk(c0, c1, E, k, store, (size_t)t, lane, topk_idx, topk_w);
+}
+
+// Returns true when the launch also selected (fused form).
+template <typename ST>
+bool launch_logits(const moe_shape& s, const void* X, const void* Wr, const float* bias,
+                   double* logits, int32_t* topk_idx, float* topk_w, hipStream_t stream) {
+#define LOGITS_LAUNCH(EPW, TPL, RT, KS, UNR, PIPE, FUSE)                                        \
+  hipLaunchKernelGGL((route_logits_kernel<ST, EPW, TPL, RT, KS, UNR, PIPE, FUSE>),              \
+                     dim3((s.T + RT * TPL - 1) / (RT * TPL), (s.E + EPW - 1) / EPW),            \
+                     dim3(KS * MOE_WAVE), 0, stream, X, Wr, bias, logits, topk_idx, topk_w,     \
+                     s.T, s.H, s.E, s.k)
+  constexpr bool wide = sizeof(ST) == 4;   // float32 rows take twice the registers per fetch
+  auto blocks = [&](int epw, int tpw) {
+    return (long)((s.T + tpw - 1) / tpw) * ((s.E + epw - 1) / epw);
+  };
+  if (s.E <= 8 && s.T <= 1024) {
+    // few experts: one workgroup per token holds all its logits and selects in
+    // the same launch; 64 lanes x 8 waves split the hidden dimension
+    const int steps = (s.H + 8 * 512 - 1) / (8 * 512);   // per wave
+    if constexpr (!wide) {
+      if (steps >= 2) { LOGITS_LAUNCH(8, 1, 1, 8, 2, false, true); return true; }
+    }
+    LOGITS_LAUNCH(8, 1, 1, 8, 1, false, true);
+    return true;
+  }
+  static const char* tune = getenv("MOE_TUNE_ROUTE_MFMA");   // measurement aid: tile threshold
+  if (blocks(16, 16) >= (tune ? atol(tune) : kMfmaTiles)) {
+    // many tokens: 16 x 16 tiles on the float64 matrix cores; enough waves
+    // along the hidden dimension to give every SIMD two
+    const long tiles = blocks(16, 16);
+    const dim3 grid((s.T + 15) / 16, (s.E + 15) / 16);
+#define MFMA_LAUNCH(KS)                                                                         \
+  hipLaunchKernelGGL((route_logits_mfma_kernel<ST, KS, wide ? 2 : 4>), grid,                    \
+                     dim3(KS * MOE_WAVE), 0, stream, X, Wr, bias, logits, s.T, s.H, s.E)
+    if (tiles * 4 >= 2048 || s.H <= 1024) MFMA_LAUNCH(4);
+    else MFMA_LAUNCH(8);
+#undef MFMA_LAUNCH
+    return false;
+  }
+  // few tokens: latency.  Eight waves split the hidden dimension and fetch all
+  // their steps at once where the registers allow; the tile is the largest
+  // that still gives every compute unit a workgroup, so that the router matrix
+  // is spread over the chip, else the smallest.
+  const int steps = (s.H + 8 * 128 - 1) / (8 * 128);   // per wave
+  const int depth = wide ? 1 : (steps >= 4 ? 4 : steps >= 2 ? 2 : 1);
+  if (blocks(4, 16) >= 256) {
+    if constexpr (!wide) { if (depth >= 2) { LOGITS_LAUNCH(4, 4, 4, 8, 2, false, false); return false; } }
+    LOGITS_LAUNCH(4, 4, 4, 8, 1, false, false);
+  } else if (blocks(4, 8) >= 256) {
+    if constexpr (!wide) {
+      if (depth == 4) { LOGITS_LAUNCH(4, 2, 4, 8, 4, false, false); return false; }
+      if (depth == 2) { LOGITS_LAUNCH(4, 2, 4, 8, 2, false, false); return false; }
+    }
+    LOGITS_LAUNCH(4, 2, 4, 8, 1, false, false);
+  } else {
+    if constexpr (!wide) {
+      if (depth == 4) { LOGITS_LAUNCH(4, 1, 4, 8, 4, false, false); return false; }
+      if (depth == 2) { LOGITS_LAUNCH(4, 1, 4, 8, 2, false, false); return false; }
+    }
+    LOGITS_LAUNCH(4, 1, 4, 8, 1, false, false);
+  }
+  return false;
+#undef LOGITS_LAUNCH
 }
 
 }  // namespace
 
+// `logits` [T,E] float64 is required: an output the caller wants, or scratch.
 moe_status launch_route(const moe_shape& s, const void* X, const void* Wr, const float* bias,
-                        int32_t* topk_idx, float* topk_w, double* logits_out,
-                        hipStream_t stream) {
+                        int32_t* topk_idx, float* topk_w, double* logits, hipStream_t stream) {
   if (s.T == 0) return MOE_OK;
-  if (s.dtype == MOE_BF16) launch_typed<uint16_t>(s, X, Wr, bias, topk_idx, topk_w, logits_out, stream);
-  else launch_typed<float>(s, X, Wr, bias, topk_idx, topk_w, logits_out, stream);
+  const bool selected = s.dtype == MOE_BF16
+      ? launch_logits<uint16_t>(s, X, Wr, bias, logits, topk_idx, topk_w, stream)
+      : launch_logits<float>(s, X, Wr, bias, logits, topk_idx, topk_w, stream);
   MOE_HIP(hipGetLastError());
+  if (!selected) {
+    hipLaunchKernelGGL(route_select_kernel, dim3((s.T + kSelectWaves - 1) / kSelectWaves),
+                       dim3(kSelectWaves * MOE_WAVE), 0, stream, logits, topk_idx, topk_w, s.T, s.E,
+                       s.k);
+    MOE_HIP(hipGetLastError());
+  }
   return MOE_OK;
 }
 
@@ -252,11 +497,18 @@ moe_status launch_route(const moe_shape& s, const void* X, const void* Wr, const
 
 extern "C" moe_status moe_route(const moe_shape* shape, const void* X, const void* Wr,
                                 const float* bias, int32_t* topk_idx, float* topk_w,
-                                double* logits_out, void* stream) {
+                                double* logits_out, void* workspace, void* stream) {
   moe_status st = moe::check_shape(shape, "moe_route");
   if (st != MOE_OK) return st;
   if (shape->T == 0) return MOE_OK;
   MOE_REQUIRE(X && Wr && topk_idx && topk_w, "moe_route: NULL pointer argument");
-  return moe::launch_route(*shape, X, Wr, bias, topk_idx, topk_w, logits_out,
+  double* logits = logits_out;
+  if (!logits) {
+    if (!workspace)
+      return moe::fail(MOE_ERR_WORKSPACE, "moe_route: needs logits_out or a workspace for the logits");
+    logits = reinterpret_cast<double*>(static_cast<char*>(workspace) +
+                                       moe::workspace_layout(*shape).logits);
+  }
+  return moe::launch_route(*shape, X, Wr, bias, topk_idx, topk_w, logits,
                            static_cast<hipStream_t>(stream));
 }

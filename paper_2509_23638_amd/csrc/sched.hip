@@ -85,7 +85,8 @@ extern "C" moe_status moe_predict_counts(const moe_shape* shape, const void* X, 
   int32_t* idx = reinterpret_cast<int32_t*>(base + w.topk_idx);
   float* wts = reinterpret_cast<float*>(base + w.topk_w);
   int32_t* count = reinterpret_cast<int32_t*>(base + w.count);
-  st = moe::launch_route(*shape, X, Wr_next, bias_next, idx, wts, nullptr, s);
+  st = moe::launch_route(*shape, X, Wr_next, bias_next, idx, wts,
+                         reinterpret_cast<double*>(base + w.logits), s);
   if (st != MOE_OK) return st;
   st = moe::launch_permute(*shape, idx, count, reinterpret_cast<int32_t*>(base + w.offset),
                            reinterpret_cast<int32_t*>(base + w.perm),

@@ -103,6 +103,23 @@ def test_route_full_size(B, name):
         _check_route(B, cfg, L, make_hidden(cfg, T=T))
 
 
+def test_route_logits_in_workspace(B):
+    """Without logits_out the logits live in the caller's workspace between
+    the two routing kernels; same indices and weights either way."""
+    cfg = SMALL[3]
+    L = make_layer(cfg)
+    sh = _shape(B, cfg)
+    idx, w, _ = _route_gpu(B, cfg, L, L["X"])
+    idx2 = torch.empty((cfg.T, cfg.k), dtype=torch.int32, device="cuda")
+    w2 = torch.empty((cfg.T, cfg.k), dtype=torch.float32, device="cuda")
+    ws = B.alloc_workspace(sh)
+    B.moe_route(sh, to_dev(L["X"]), to_dev(L["Wr"]), to_dev(L["b"]), idx2, w2, None, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx2.cpu().numpy(), idx) and np.array_equal(w2.cpu().numpy(), w)
+    with pytest.raises(B.MoEError):
+        B.moe_route(sh, to_dev(L["X"]), to_dev(L["Wr"]), to_dev(L["b"]), idx2, w2, None, None)
+
+
 def test_route_exact_ties(B):
     """Wr = 0 makes the logits equal the bias, which repeats values: every
     round must take the lowest index among equals."""
