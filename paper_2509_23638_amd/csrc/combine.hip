@@ -15,8 +15,8 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
                                                       const void* __restrict__ residual,
                                                       void* __restrict__ out, int T, int H, int k,
                                                       int S) {
-  const int t = blockIdx.y;
-  const int h4 = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  const int t = blockIdx.x;            // tokens along x: the only grid dimension that can hold 2^24
+  const int h4 = (blockIdx.y * blockDim.x + threadIdx.x) * 4;
   if (h4 >= H) return;
   const int A = T * k;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -61,7 +61,7 @@ moe_status launch_combine(const moe_shape& s, const float* Y, const float* topk_
                           const int32_t* inv_perm, const void* residual, void* out,
                           hipStream_t stream) {
   if (s.T == 0) return MOE_OK;
-  dim3 grid((s.H / 4 + 255) / 256, s.T), block(256);
+  dim3 grid(s.T, (s.H / 4 + 255) / 256), block(256);
   if (s.dtype == MOE_BF16)
     hipLaunchKernelGGL(combine_kernel<true>, grid, block, 0, stream, Y, topk_w, inv_perm, residual,
                        out, s.T, s.H, s.k, s.S);

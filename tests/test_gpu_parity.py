@@ -52,16 +52,26 @@ SMALL = [
     _small("s_bf16_ragged", T=150, E=2, k=1, H=384, F=256),       # > 64 rows per expert
     _small("s_bf16_many", T=33, E=60, k=4, H=128, F=128, S=1, bias="zipf", bias_scale=1.1),
     _small("s_bf16_e128", T=17, E=128, k=8, H=256, F=128),
+    _small("s_bf16_limits", T=5, E=128, k=16, S=8, H=128, F=128),      # every documented maximum
     _small("s_bf16_big_blocks", T=300, E=4, k=2, H=256, F=384, S=1),   # > 128 rows per expert
     _small("s_bf16_odd_chunks", T=20, E=4, k=1, H=128, F=1408, bias="none"),  # 11 k-chunks of 128
     _small("s_bf16_one", T=1, E=8, k=2),
     _small("s_bf16_k_eq_e", T=9, E=3, k=3),
     _small("s_f32", dtype="f32", T=19, H=64, F=96, S=1),
     _small("s_f32_e1", dtype="f32", T=5, E=1, k=1, H=72, F=40),
-    # >= 96 tokens take the matrix-core router: ragged hidden size, E past a tile, E = 128
-    _small("s_f32_mfma_route", dtype="f32", T=130, E=5, k=2, H=72, F=40),
-    _small("s_bf16_mfma_route_e128", T=100, E=128, k=8, H=256, F=128),
-    _small("s_bf16_mfma_route_e20", T=97, E=20, k=3, H=384, F=128, S=1),
+    # many tokens x experts take the matrix-core router: ragged hidden size, ragged tiles, E = 128
+    _small("s_f32_mfma_route", dtype="f32", T=530, E=60, k=2, H=72, F=40),
+    _small("s_bf16_mfma_route_e128", T=260, E=128, k=8, H=256, F=128),
+    _small("s_bf16_mfma_route_e20", T=1030, E=20, k=3, H=384, F=128, S=1),
+    # few tokens, many experts: every tile of the vector router (1, 2, 4 tokens per lane)
+    _small("s_bf16_route_t3_e60", T=3, E=60, k=4, H=384, F=128),
+    _small("s_bf16_route_t40_e100", T=40, E=100, k=5, H=1152, F=128),
+    _small("s_f32_route_e12", dtype="f32", T=70, E=12, k=3, H=200, F=40),
+    _small("s_bf16_route_4tok_lane", T=130, E=128, k=8, H=256, F=128),
+    _small("s_bf16_route_2tok_lane", T=70, E=128, k=8, H=2176, F=128),
+    _small("s_bf16_route_deep", T=20, E=60, k=4, H=4224, F=128),
+    _small("s_bf16_route_mfma_8waves", T=260, E=128, k=8, H=2176, F=128),
+    _small("s_bf16_route_fused_long", T=6, E=8, k=2, H=4224, F=128),
 ]
 
 
