@@ -43,8 +43,8 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
       acc.w += __uint_as_float(r.y & 0xffff0000u);
     }
     uint2 o;
-    o.x = (uint32_t)f32_to_bf16_bits(acc.x) | ((uint32_t)f32_to_bf16_bits(acc.y) << 16);
-    o.y = (uint32_t)f32_to_bf16_bits(acc.z) | ((uint32_t)f32_to_bf16_bits(acc.w) << 16);
+    o.x = pack_bf16x2(acc.x, acc.y);
+    o.y = pack_bf16x2(acc.z, acc.w);
     *reinterpret_cast<uint2*>(static_cast<uint16_t*>(out) + (size_t)t * H + h4) = o;
   } else {
     if (residual) {

@@ -101,4 +101,16 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
   return (uint16_t)(u >> 16);
 }
 
+// Two float32 values to packed bfloat16 (lo in bits 0..15), round to nearest
+// even: one v_cvt_pk_bf16_f32.  Bit-identical to f32_to_bf16_bits for every
+// finite input (checked exhaustively over the high halves with the tie and
+// near-tie low halves).
+typedef __bf16 bf16x2_hw __attribute__((ext_vector_type(2)));
+typedef float f32x2_hw __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  const f32x2_hw v = {lo, hi};
+  const bf16x2_hw b = __builtin_convertvector(v, bf16x2_hw);
+  return __builtin_bit_cast(uint32_t, b);
+}
+
 }  // namespace moe

@@ -27,6 +27,8 @@
 
 #include <stdlib.h>
 
+#include <algorithm>
+
 namespace moe {
 namespace {
 
@@ -67,7 +69,11 @@ __device__ __forceinline__ size_t weight_lane_offset(bool tiled, int n16, int K,
 }
 __device__ __forceinline__ int weight_kstep_stride(bool tiled) { return tiled ? 512 : kKStep; }
 
-__device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
+// silu(z) = z / (1 + e^-z) with the hardware exponential and reciprocal (1 ulp
+// each): the result is rounded to bfloat16 right after.
+__device__ __forceinline__ float silu_f(float z) {
+  return z * __builtin_amdgcn_rcpf(1.0f + __expf(-z));
+}
 
 // RT = 16-row weight tiles per wave and matrix.  A wave holds NA = 2*RT weight
 // tiles: gate/up -> tile 2*rt + m is rows (wave*RT + rt)*16.. of Wg (m = 0) or
@@ -247,13 +253,12 @@ __device__ __forceinline__ void ffn_block(const FfnArgs& a, const uint16_t* W0, 
       uint16_t* h = static_cast<uint16_t*>(a.out);
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
-        uint16_t hb[4];
+        float hv[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-          hb[j] = f32_to_bf16_bits(silu_f(st.acc[2 * rt][t][j]) * st.acc[2 * rt + 1][t][j]);
+        for (int j = 0; j < 4; ++j) hv[j] = silu_f(st.acc[2 * rt][t][j]) * st.acc[2 * rt + 1][t][j];
         uint2 pk;
-        pk.x = (uint32_t)hb[0] | ((uint32_t)hb[1] << 16);
-        pk.y = (uint32_t)hb[2] | ((uint32_t)hb[3] << 16);
+        pk.x = pack_bf16x2(hv[0], hv[1]);
+        pk.y = pack_bf16x2(hv[2], hv[3]);
         *reinterpret_cast<uint2*>(h + (size_t)p * a.N + nrow[2 * rt] + 4 * g) = pk;
       }
     } else if (MODE == kDownHalves) {
@@ -392,75 +397,129 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
   }
 }
 
-// NJ = token tiles per wave that are multiplied (the block's tiles, taken
-// alternately by the two wave rows, rounded up): a compile-time bound, so the
-// accumulators stay in registers and a short block costs what it uses.
-template <int MODE, int NJ>
-__device__ __forceinline__ void ffn_tile_block(const FfnArgs& a, const ExpertTable& tab, int e,
-                                               int r0, int row_end, int slab,
-                                               unsigned char* ring) {
-  const int shared_base = e >= a.E ? a.A + (e - a.E) * a.T : -1;
-  const int lane = threadIdx.x & (MOE_WAVE - 1), wave = threadIdx.x / MOE_WAVE;
-  const int wm = wave & 1, wn = wave >> 1;
-  const int n0 = slab * (MODE == kGateUp ? 64 : 128);
+// One work item of the tiled kernel: a 256-row block of an expert's bucket
+// times one slab of its weight rows.
+struct TileItem {
+  int e, r0, row_end, slab;
+};
 
-  // Blocks of a stage: 0..15 = token tiles, 16..23 = weight tiles (gate/up:
-  // 16..19 gate rows n0.., 20..23 the same rows of up).  Every block is two
-  // fetches (rows 0..7 and 8..15); wave w issues the fetches h = w + 4 q.
-  const uint16_t* src[kFetchPerWave];
-  {
-    const int row8 = lane >> 3, slot = lane & 7;
+__device__ __forceinline__ TileItem tile_item(const GroupList& groups, const int32_t* plan, int item,
+                                              int slabs) {
+  const int blk = item / slabs;
+  TileItem it;
+  it.slab = item - blk * slabs;
+  it.e = groups.id[plan[1 + 3 * blk]];
+  it.r0 = plan[2 + 3 * blk];
+  it.row_end = plan[3 + 3 * blk];
+  return it;
+}
+
+// Blocks of a stage: 0..15 = token tiles, 16..23 = weight tiles (gate/up:
+// 16..19 gate rows n0.., 20..23 the same rows of up).  Every block is two
+// fetches (rows 0..7 and 8..15); wave w issues the fetches h = w + 4 q, so its
+// fetches q < 8 are token rows and q >= 8 weight rows.
+//
+// First half of an item's set-up: what names the activation row behind each
+// of this lane's eight token fetches (gate/up: a bucket position maps to its
+// token through perm -- loads that are issued early and used late).
+template <int MODE>
+__device__ __forceinline__ void tile_rows(const FfnArgs& a, const TileItem& it, int lane, int wave,
+                                          int (&ids)[8]) {
+  const int row8 = lane >> 3;
 #pragma unroll
-    for (int q = 0; q < kFetchPerWave; ++q) {
-      const int h = wave + 4 * q, blk = h >> 1, u = h & 1;
-      const int chunk = slot ^ (u ? ((row8 + 1) & 7) : row8);
-      const int rr = 8 * u + row8;   // row inside the 16-row block
-      const uint16_t* rowp;
-      if (blk >= 16 && a.tiled) {
-        // tiled weights: fetch u is the MFMA tile of k-step 2 st + u, one KiB in a row
-        const int j = blk - 16;
-        const uint16_t* W;
-        int n16;
-        if (MODE == kGateUp) {
-          W = static_cast<const uint16_t*>(j < 4 ? tab.Wg[e] : tab.Wu[e]);
-          n16 = n0 / 16 + (j & 3);
-        } else {
-          W = static_cast<const uint16_t*>(tab.Wd[e]);
-          n16 = n0 / 16 + j;
-        }
-        src[q] = W + weight_lane_offset(true, n16, a.K, lane) + (size_t)u * 512;
-        continue;
-      }
-      if (blk < 16) {
-        const int p = min(r0 + blk * 16 + rr, row_end - 1);
-        int row;
-        if (MODE == kGateUp) row = shared_base >= 0 ? p - shared_base : a.perm[p] / a.k;
-        else row = p;
-        rowp = a.act + (size_t)row * a.K;
+  for (int q = 0; q < 8; ++q) {
+    const int h = wave + 4 * q, blk = h >> 1, u = h & 1;
+    const int p = min(it.r0 + blk * 16 + 8 * u + row8, it.row_end - 1);
+    // Unconditional, branch-free loads with no consumer nearby, so that they
+    // stay in flight: a shared expert's rows (p >= A) read a valid entry that
+    // is ignored later, and the division by k waits until the id is used.
+    ids[q] = MODE == kGateUp ? a.perm[min(p, a.A - 1)] : 0;
+  }
+}
+
+// Second half: the twelve source pointers of this lane (stage 0).
+template <int MODE>
+__device__ __forceinline__ void tile_sources(const FfnArgs& a, const ExpertTable& tab,
+                                             const TileItem& it, const int (&ids)[8], int lane,
+                                             int wave, const uint16_t* (&src)[kFetchPerWave]) {
+  const int e = it.e;
+  const int n0 = it.slab * (MODE == kGateUp ? 64 : 128);
+  const int row8 = lane >> 3, slot = lane & 7;
+#pragma unroll
+  for (int q = 0; q < kFetchPerWave; ++q) {
+    const int h = wave + 4 * q, blk = h >> 1, u = h & 1;
+    const int chunk = slot ^ (u ? ((row8 + 1) & 7) : row8);
+    const int rr = 8 * u + row8;   // row inside the 16-row block
+    if (q < 8) {
+      const int p = min(it.r0 + blk * 16 + rr, it.row_end - 1);   // bucket position
+      int row = p;                                                 // down: h is in bucket order
+      if (MODE == kGateUp) row = e >= a.E ? p - (a.A + (e - a.E) * a.T) : ids[q] / a.k;
+      src[q] = a.act + (size_t)row * a.K + chunk * 8;
+      continue;
+    }
+    const int j = blk - 16;
+    if (a.tiled) {
+      // tiled weights: fetch u is the MFMA tile of k-step 2 st + u, one KiB in a row
+      const uint16_t* W;
+      int n16;
+      if (MODE == kGateUp) {
+        W = static_cast<const uint16_t*>(j < 4 ? tab.Wg[e] : tab.Wu[e]);
+        n16 = n0 / 16 + (j & 3);
       } else {
-        const int j = blk - 16;
-        if (MODE == kGateUp) {
-          const uint16_t* W = static_cast<const uint16_t*>(j < 4 ? tab.Wg[e] : tab.Wu[e]);
-          rowp = W + (size_t)(n0 + (j & 3) * 16 + rr) * a.K;
-        } else {
-          rowp = static_cast<const uint16_t*>(tab.Wd[e]) + (size_t)(n0 + j * 16 + rr) * a.K;
-        }
+        W = static_cast<const uint16_t*>(tab.Wd[e]);
+        n16 = n0 / 16 + j;
+      }
+      src[q] = W + weight_lane_offset(true, n16, a.K, lane) + (size_t)u * 512;
+    } else {
+      const uint16_t* rowp;
+      if (MODE == kGateUp) {
+        const uint16_t* W = static_cast<const uint16_t*>(j < 4 ? tab.Wg[e] : tab.Wu[e]);
+        rowp = W + (size_t)(n0 + (j & 3) * 16 + rr) * a.K;
+      } else {
+        rowp = static_cast<const uint16_t*>(tab.Wd[e]) + (size_t)(n0 + j * 16 + rr) * a.K;
       }
       src[q] = rowp + chunk * 8;
     }
   }
-  // elements a source pointer advances per 64-wide stage: 64 along its row,
-  // or two KiB tiles for tiled weights (fetches 4.. of a wave are weights when
-  // h >= 32, i.e. q >= 8)
-  const int w_adv = a.tiled ? 1024 : kTileK;
-  auto fetch = [&](int st) {
-    unsigned char* base = ring + (st % kTileStages) * kTileStage;
+  // pin the pointers down here: otherwise their computation (with its waits
+  // for table look-ups) sinks in between the fetches, and an in-order wait
+  // there stalls on the fetches already issued
 #pragma unroll
-    for (int q = 0; q < kFetchPerWave; ++q)
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(src[q] + (size_t)st * (q >= 8 ? w_adv : kTileK)),
-          (__attribute__((address_space(3))) void*)(base + (wave + 4 * q) * kFragBytes), 16, 0, 0);
-  };
+  for (int q = 0; q < kFetchPerWave; ++q) asm volatile("" : "+v"(src[q]));
+}
+
+// Issue this wave's twelve fetches of stage st into ring buffer st % 3.  A
+// source pointer advances 64 elements along its row per stage, or two KiB
+// tiles for tiled weights.
+__device__ __forceinline__ void tile_fetch(const uint16_t* const (&src)[kFetchPerWave], int st,
+                                           int w_adv, int wave, unsigned char* ring) {
+  unsigned char* base = ring + (st % kTileStages) * kTileStage;
+#pragma unroll
+  for (int q = 0; q < kFetchPerWave; ++q)
+    __builtin_amdgcn_global_load_lds(
+        (const __attribute__((address_space(1))) void*)(src[q] + (size_t)st * (q >= 8 ? w_adv : kTileK)),
+        (__attribute__((address_space(3))) void*)(base + (wave + 4 * q) * kFragBytes), 16, 0, 0);
+}
+
+// One item.  On entry the fetches of its stages 0 and 1 are in flight (issued
+// by the previous item, or by the kernel's preamble); before its own epilogue
+// it sets up the next item of this workgroup and issues that item's first two
+// stages, so the stores of one item and the cold first fetches of the next
+// overlap instead of adding up.
+// NJ = token tiles per wave that are multiplied (the block's tiles, taken
+// alternately by the two wave rows, rounded up): a compile-time bound, so the
+// accumulators stay in registers and a short block costs what it uses.
+template <int MODE, int NJ>
+__device__ __forceinline__ void ffn_tile_block(const FfnArgs& a, const ExpertTable& tab,
+                                               const TileItem& it, bool has_next,
+                                               const TileItem& nxt,
+                                               const uint16_t* (&src)[kFetchPerWave],
+                                               unsigned char* ring) {
+  const int r0 = it.r0, row_end = it.row_end;
+  const int lane = threadIdx.x & (MOE_WAVE - 1), wave = threadIdx.x / MOE_WAVE;
+  const int wm = wave & 1, wn = wave >> 1;
+  const int n0 = it.slab * (MODE == kGateUp ? 64 : 128);
+  const int w_adv = a.tiled ? 1024 : kTileK;
   // where lane (r, g) finds row r, chunk 4 s + g of a block, for k-step s = 0, 1
   int rd[2];
   {
@@ -480,16 +539,27 @@ __device__ __forceinline__ void ffn_tile_block(const FfnArgs& a, const ExpertTab
 #pragma unroll
     for (int j = 0; j < NJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+  int next_ids[8];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) next_ids[q] = 0;
+
   const int ns = a.K / kTileK;
-  fetch(0);
-  if (ns > 1) fetch(1);
   for (int st = 0; st < ns; ++st) {
     // this wave's fetches of stage st have landed once at most the fetches of
     // the one younger stage already issued are still outstanding
-    if (st + 1 < ns) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();   // everybody's fetches of stage st landed; stage st-1 has been consumed
-    if (st + 2 < ns) fetch(st + 2);   // into the buffer stage st-1 used
+    // A bare barrier, not __syncthreads(): the fence that comes with the latter
+    // makes the compiler wait for EVERY outstanding fetch (the ones of the next
+    // stages too), which would put the whole ring one stage deep.  What the
+    // barrier has to order is covered by hand: the vmcnt wait above it (this
+    // wave's direct-to-LDS fetches of stage st have been written), and program
+    // order (a wave's LDS reads of stage st-1 fed MFMAs it has already issued).
+    if (st + 1 < ns) asm volatile("s_waitcnt vmcnt(12)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    // the next item's row look-ups: issued early (ahead of this stage's fetches, so
+    // that the in-order wait above never has to wait for more than one stage of
+    // fetches), needed only after the last stage
+    if (st == 1 && has_next) tile_rows<MODE>(a, nxt, lane, wave, next_ids);
+    if (st + 2 < ns) tile_fetch(src, st + 2, w_adv, wave, ring);   // into the buffer stage st-1 used
     const unsigned char* base = ring + (st % kTileStages) * kTileStage;
     // LDS reads of both k-steps are issued up front, in order; the MFMAs of the
     // first k-step only wait for its own operands (LDS returns in order), so the
@@ -527,57 +597,97 @@ __device__ __forceinline__ void ffn_tile_block(const FfnArgs& a, const ExpertTab
   }
 
   // D layout: lane holds rows 4*g .. 4*g+3 of the 16-row weight tile, column r = token
-  const int r = lane & 15, g = lane >> 4;
+  auto epilogue = [&]() {
+    const int r = lane & 15, g = lane >> 4;
 #pragma unroll
-  for (int j = 0; j < NJ; ++j) {
-    const int p = r0 + (wm + 2 * j) * 16 + r;
-    if (p >= row_end) continue;
-    if (MODE == kGateUp) {
-      uint16_t* h = static_cast<uint16_t*>(a.out);
+    for (int j = 0; j < NJ; ++j) {
+      const int p = r0 + (wm + 2 * j) * 16 + r;
+      if (p >= row_end) continue;
+      if (MODE == kGateUp) {
+        uint16_t* h = static_cast<uint16_t*>(a.out);
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        uint16_t hb[4];
+        for (int i = 0; i < 2; ++i) {
+          float hv[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) hb[q] = f32_to_bf16_bits(silu_f(acc[i][j][q]) * acc[2 + i][j][q]);
-        uint2 pk;
-        pk.x = (uint32_t)hb[0] | ((uint32_t)hb[1] << 16);
-        pk.y = (uint32_t)hb[2] | ((uint32_t)hb[3] << 16);
-        *reinterpret_cast<uint2*>(h + (size_t)p * a.N + n0 + (wn * 2 + i) * 16 + 4 * g) = pk;
+          for (int q = 0; q < 4; ++q) hv[q] = silu_f(acc[i][j][q]) * acc[2 + i][j][q];
+          uint2 pk;
+          pk.x = pack_bf16x2(hv[0], hv[1]);
+          pk.y = pack_bf16x2(hv[2], hv[3]);
+          *reinterpret_cast<uint2*>(h + (size_t)p * a.N + n0 + (wn * 2 + i) * 16 + 4 * g) = pk;
+        }
+      } else {
+        float* y = static_cast<float*>(a.out);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          *reinterpret_cast<float4*>(y + (size_t)p * a.N + n0 + (wn * 4 + i) * 16 + 4 * g) =
+              make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
       }
-    } else {
-      float* y = static_cast<float*>(a.out);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        *reinterpret_cast<float4*>(y + (size_t)p * a.N + n0 + (wn * 4 + i) * 16 + 4 * g) =
-            make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
     }
+  };
+
+  // The ring is free once every wave has read the last stage: start the next
+  // item, then write this one's results while those fetches fly.  (The
+  // epilogue is written out on both paths: behind the join of a conditional
+  // the compiler would first wait for every outstanding fetch.)
+  if (has_next) {
+    const uint16_t* next_src[kFetchPerWave];
+    if (ns < 2) tile_rows<MODE>(a, nxt, lane, wave, next_ids);
+    tile_sources<MODE>(a, tab, nxt, next_ids, lane, wave, next_src);
+    asm volatile("s_barrier" ::: "memory");
+    tile_fetch(next_src, 0, w_adv, wave, ring);
+    if (ns > 1) tile_fetch(next_src, 1, w_adv, wave, ring);
+    epilogue();
+#pragma unroll
+    for (int q = 0; q < kFetchPerWave; ++q) src[q] = next_src[q];
+  } else {
+    epilogue();
   }
 }
 
+// Persistent workgroups, one per compute unit (the 144 KiB ring allows no
+// more).  Work items = (row block, weight slab), slab fastest.  Workgroups are
+// dealt to the 8 XCDs round-robin by their linear id, and every XCD has its
+// own L2: each XCD gets one contiguous eighth of the items, and the
+// workgroups behind one L2 walk that run side by side, so the slabs that share
+// a row block's activations (and the row blocks that share a shared expert's
+// weights) are in flight together.
 template <int MODE>
 __global__ __launch_bounds__(kThreads, 1) void ffn_tile_kernel(FfnArgs a, ExpertTable tab,
                                                                GroupList groups,
                                                                const int32_t* __restrict__ plan) {
   extern __shared__ __attribute__((aligned(16))) unsigned char ring[];
-  // Work items = (row block, weight slab), slab fastest.  Workgroups are dealt
-  // to the 8 XCDs round-robin by their linear id, and every XCD has its own
-  // L2: give each XCD one contiguous eighth of the items, so that the slabs
-  // that share a row block's activations (and the row blocks that share a
-  // shared expert's weights) run next to each other behind the same L2.
   const int slabs = a.N / (MODE == kGateUp ? 64 : 128);
   const int total = plan[0] * slabs;
   const int per_xcd = (total + 7) / 8;
-  const int local = blockIdx.x >> 3;
-  const int item = (blockIdx.x & 7) * per_xcd + local;
-  if (local >= per_xcd || item >= total) return;
-  const int blk = item / slabs, slab = item - blk * slabs;
-  const int e = groups.id[plan[1 + 3 * blk]];
-  const int r0 = plan[2 + 3 * blk], row_end = plan[3 + 3 * blk];
-  const int tiles = (min(row_end - r0, kTileRows) + 15) / 16;
-  if (tiles <= 4) ffn_tile_block<MODE, 2>(a, tab, e, r0, row_end, slab, ring);
-  else if (tiles <= 8) ffn_tile_block<MODE, 4>(a, tab, e, r0, row_end, slab, ring);
-  else if (tiles <= 12) ffn_tile_block<MODE, 6>(a, tab, e, r0, row_end, slab, ring);
-  else ffn_tile_block<MODE, 8>(a, tab, e, r0, row_end, slab, ring);
+  const int xcd = blockIdx.x & 7, stride = gridDim.x >> 3;   // grid is a multiple of 8
+  int local = blockIdx.x >> 3;
+  const int lo = xcd * per_xcd, hi = min(lo + per_xcd, total);
+  if (lo + local >= hi) return;
+  const int lane = threadIdx.x & (MOE_WAVE - 1), wave = threadIdx.x / MOE_WAVE;
+  const int w_adv = a.tiled ? 1024 : kTileK;
+
+  TileItem it = tile_item(groups, plan, lo + local, slabs);
+  const uint16_t* src[kFetchPerWave];
+  {
+    int rows[8];
+    tile_rows<MODE>(a, it, lane, wave, rows);
+    tile_sources<MODE>(a, tab, it, rows, lane, wave, src);
+    tile_fetch(src, 0, w_adv, wave, ring);
+    if (a.K / kTileK > 1) tile_fetch(src, 1, w_adv, wave, ring);
+  }
+  while (true) {
+    const bool has_next = lo + local + stride < hi;
+    TileItem nxt = it;
+    if (has_next) nxt = tile_item(groups, plan, lo + local + stride, slabs);
+    const int tiles = (min(it.row_end - it.r0, kTileRows) + 15) / 16;
+    if (tiles <= 4) ffn_tile_block<MODE, 2>(a, tab, it, has_next, nxt, src, ring);
+    else if (tiles <= 8) ffn_tile_block<MODE, 4>(a, tab, it, has_next, nxt, src, ring);
+    else if (tiles <= 12) ffn_tile_block<MODE, 6>(a, tab, it, has_next, nxt, src, ring);
+    else ffn_tile_block<MODE, 8>(a, tab, it, has_next, nxt, src, ring);
+    if (!has_next) break;
+    it = nxt;
+    local += stride;
+  }
 }
 
 
@@ -598,7 +708,14 @@ moe_status launch_tile(const moe_shape& s, const FfnArgs& args, const ExpertTabl
   hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, stream, args.offset, s.T, s.E, args.A,
                      groups, plan);
   const int slabs = MODE == kGateUp ? s.F / 64 : s.H / 128;
-  const int grid = (slabs * max_row_blocks(s) + 7) / 8 * 8;
+  // one persistent workgroup per compute unit, never more than there can be items
+  static int n_cu = 0;
+  if (!n_cu) {
+    int dev = 0;
+    MOE_HIP(hipGetDevice(&dev));
+    MOE_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+  }
+  const int grid = (std::min(slabs * max_row_blocks(s), n_cu) + 7) / 8 * 8;
   hipLaunchKernelGGL((ffn_tile_kernel<MODE>), dim3(grid), dim3(kThreads), kTileLds, stream, args,
                      tab, groups, plan);
   MOE_HIP(hipGetLastError());
