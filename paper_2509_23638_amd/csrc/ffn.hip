@@ -102,7 +102,7 @@ struct Streamer {
   size_t act_off[NT];     // element offset of this lane's activation row per tile
   static constexpr int NS = (RT == 1 && !kHalves) ? 3 : 2;   // weight chunks held: c .. c+NS-1
   bf16x8 wreg[NS][kStepsPerChunk][NA];
-  uint4 xreg[NH * NT];
+  uint4 xreg[NS][NH * NT];   // activation fetches in flight, by chunk modulo NS
   f32x4 acc[NA][NT];
 
   __device__ __forceinline__ Streamer(const FfnArgs& a_) : a(a_) {}
@@ -118,21 +118,23 @@ struct Streamer {
   }
 
   // wave w fetches k-step w of every tile of chunk c
+  template <int SET>
   __device__ __forceinline__ void load_act(int c) {
 #pragma unroll
     for (int hf = 0; hf < NH; ++hf)
 #pragma unroll
       for (int t = 0; t < NT; ++t)
-        xreg[hf * NT + t] = *reinterpret_cast<const uint4*>(
+        xreg[SET][hf * NT + t] = *reinterpret_cast<const uint4*>(
             a.act + act_off[t] + (size_t)(c + hf * half_chunks) * kChunk + wave * kKStep +
             (lane >> 4) * 8);
   }
 
+  template <int SET>
   __device__ __forceinline__ void store_act(int buf) {
 #pragma unroll
     for (int q = 0; q < NH * NT; ++q)
       *reinterpret_cast<uint4*>(lds + buf * kBufBytes +
-                                ((q * kStepsPerChunk + wave) * MOE_WAVE + lane) * 16) = xreg[q];
+                                ((q * kStepsPerChunk + wave) * MOE_WAVE + lane) * 16) = xreg[SET][q];
   }
 
   template <int SET>
@@ -160,18 +162,19 @@ struct Streamer {
   }
 
   // Chunk c multiplies while the weights of the next NS-1 chunks are in flight.
-  // With three register sets and two waves per SIMD about 128 KB per compute
-  // unit are on their way from HBM, enough to cover the memory latency; the
-  // two-tile variant has no registers left for a third set.  The activations
-  // of chunk c+1 come from L2; their fetch is issued before the weight fetch
-  // because it is waited for first (loads complete in order).
+  // Loads complete in order, so what a wait lets stay in flight is whatever was
+  // issued after the thing waited for.  The activations of chunk c+1 are
+  // written to LDS at the end of step c; they were fetched a whole step
+  // earlier, AHEAD of the weights of chunks c+1 and c+2, so waiting for them
+  // leaves both of those weight chunks on their way (fetched in the same step,
+  // behind the newest weights, they would drain the pipe down to one chunk at
+  // every step).
   template <int SET>
   __device__ __forceinline__ void step(int c, int nchunks) {
-    const bool more = c + 1 < nchunks;
-    if (more) load_act(c + 1);
+    if (c + 2 < nchunks) load_act<(SET + 2) % NS>(c + 2);
     if (c + NS - 1 < nchunks) load_weights<(SET + NS - 1) % NS>(c + NS - 1);
     multiply<SET>(c & 1);
-    if (more) store_act((c + 1) & 1);
+    if (c + 1 < nchunks) store_act<(SET + 1) % NS>((c + 1) & 1);
     __syncthreads();
   }
 
@@ -181,10 +184,11 @@ struct Streamer {
     for (int i = 0; i < NA; ++i)
 #pragma unroll
       for (int t = 0; t < NT; ++t) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    load_act(0);
+    load_act<0>(0);
     load_weights<0>(0);
+    if (nchunks > 1) load_act<1>(1);
     if (NS == 3 && nchunks > 1) load_weights<1>(1);
-    store_act(0);
+    store_act<0>(0);
     __syncthreads();
     int c = 0;
     if (NS == 3) {
