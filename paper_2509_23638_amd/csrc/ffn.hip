@@ -340,13 +340,9 @@ __global__ __launch_bounds__(kThreads) void ffn_stream_kernel(FfnArgs a, ExpertT
 // Fetch shape.  Measured on this chip, a wave-wide 16-byte load whose lanes
 // cover 16 rows x 64 B runs at a third of the rate of one that covers 8 rows x
 // 128 B (whole cache lines), even out of L2.  So one fetch instruction takes 8
-// rows x 64 k, and a 16-row x 64-k operand block is two of them (2 KiB).  The
-// hardware stores lane l at base + 16 l; which 16-byte chunk of its row a lane
-// fetches is ours to choose, so the chunks are XOR-swizzled: lane (row8 = l/8,
-// slot = l%8) of half u fetches chunk slot ^ sw, sw = row8 for the upper half
-// and (row8 + 1) % 8 for the lower.  The MFMA operand read -- lane (r, g) wants
-// row r, chunk 4 s + g of k-step s -- then spreads its sixteen rows over all
-// LDS banks instead of piling them on eight.
+// rows x 64 k, and a 16-row x 64-k operand block is two of them (2 KiB).  Where
+// the rows and chunks of a block sit inside those 2 KiB is chosen for the LDS
+// banks (see tile_fetch_row below).
 //
 // The waves take the token tiles alternately so that a partly filled 256-row
 // block is still shared evenly; tiles past the bucket's end are fetched
@@ -401,6 +397,34 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
   }
 }
 
+// Placement of a 16-row x 64-k operand block in LDS (2 KiB = two fetches).
+// The direct-to-LDS load puts fetch lane l at base + 16 l, and a fetch should
+// cover whole 128-byte lines, so lanes 8 j .. 8 j + 7 take the eight 16-byte
+// chunks of one row: row slot j, chunk position i.  Which row sits in which
+// slot and which chunk at which position is free, and decides the bank
+// behaviour of the MFMA operand read, where lane (r, g) wants row r, chunk
+// 4 s + g.  Measured on this chip, a ds_read_b128 runs at the full 256 B/clk
+// only if (a) every four consecutive lanes read four different 16-byte slots
+// of ONE aligned 64-byte bank group, and (b) the eight such quads of a
+// 32-lane half cover the four bank groups evenly; rows of 128 bytes with an
+// XOR swizzle, conflict-free by the usual bank arithmetic, break (a) and run at
+// half rate.  So: rows 4 q + idx (idx = 0..3) of quad q go to fetch q / 2, row
+// slots 2 idx + (q & 1) (same parity = same half of the 256-byte bank line),
+// and chunk c sits at position 4 (c & 1) + ((c >> 1) ^ idx): the four rows of
+// a quad land in one bank group, g = c & 1 selects which.
+__device__ __forceinline__ int tile_fetch_row(int lane, int u) {
+  const int j = lane >> 3;
+  return 4 * (2 * u + (j & 1)) + (j >> 1);
+}
+__device__ __forceinline__ int tile_fetch_chunk(int lane) {
+  const int j = lane >> 3, i = lane & 7;
+  return 2 * ((i & 3) ^ (j >> 1)) + (i >> 2);
+}
+__device__ __forceinline__ int tile_read_offset(int r, int c) {
+  const int q = r >> 2, idx = r & 3;
+  return (q >> 1) * kFragBytes + (2 * idx + (q & 1)) * 128 + (4 * (c & 1) + (((c >> 1) ^ idx) & 3)) * 16;
+}
+
 // One work item of the tiled kernel: a 256-row block of an expert's bucket
 // times one slab of its weight rows.
 struct TileItem {
@@ -429,11 +453,10 @@ __device__ __forceinline__ TileItem tile_item(const GroupList& groups, const int
 template <int MODE>
 __device__ __forceinline__ void tile_rows(const FfnArgs& a, const TileItem& it, int lane, int wave,
                                           int (&ids)[8]) {
-  const int row8 = lane >> 3;
 #pragma unroll
   for (int q = 0; q < 8; ++q) {
     const int h = wave + 4 * q, blk = h >> 1, u = h & 1;
-    const int p = min(it.r0 + blk * 16 + 8 * u + row8, it.row_end - 1);
+    const int p = min(it.r0 + blk * 16 + tile_fetch_row(lane, u), it.row_end - 1);
     // Unconditional, branch-free loads with no consumer nearby, so that they
     // stay in flight: a shared expert's rows (p >= A) read a valid entry that
     // is ignored later, and the division by k waits until the id is used.
@@ -448,12 +471,11 @@ __device__ __forceinline__ void tile_sources(const FfnArgs& a, const ExpertTable
                                              int wave, const uint16_t* (&src)[kFetchPerWave]) {
   const int e = it.e;
   const int n0 = it.slab * (MODE == kGateUp ? 64 : 128);
-  const int row8 = lane >> 3, slot = lane & 7;
+  const int chunk = tile_fetch_chunk(lane);
 #pragma unroll
   for (int q = 0; q < kFetchPerWave; ++q) {
     const int h = wave + 4 * q, blk = h >> 1, u = h & 1;
-    const int chunk = slot ^ (u ? ((row8 + 1) & 7) : row8);
-    const int rr = 8 * u + row8;   // row inside the 16-row block
+    const int rr = tile_fetch_row(lane, u);   // row inside the 16-row block
     if (q < 8) {
       const int p = min(it.r0 + blk * 16 + rr, it.row_end - 1);   // bucket position
       int row = p;                                                 // down: h is in bucket order
@@ -526,12 +548,8 @@ __device__ __forceinline__ void ffn_tile_block(const FfnArgs& a, const ExpertTab
   const int w_adv = a.tiled ? 1024 : kTileK;
   // where lane (r, g) finds row r, chunk 4 s + g of a block, for k-step s = 0, 1
   int rd[2];
-  {
-    const int r = lane & 15, g = lane >> 4;
-    const int u = r >> 3, row8 = r & 7, sw = u ? ((row8 + 1) & 7) : row8;
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) rd[ks] = u * kFragBytes + (row8 * 8 + ((4 * ks + g) ^ sw)) * 16;
-  }
+  for (int ks = 0; ks < 2; ++ks) rd[ks] = tile_read_offset(lane & 15, 4 * ks + (lane >> 4));
   // tiled weights arrive as whole MFMA tiles: k-step ks is the ks-th KiB of the block
   int rdw[2];
 #pragma unroll
