@@ -467,3 +467,33 @@ def test_batch_independence_bitwise(B):
     one = _layer_gpu(B, cfg, dict(L, X=L["X"][7:8]))
     assert np.array_equal(one["topk_idx"][0], full["topk_idx"][7])
     assert row_rel_err(one["out"], full["out"][7:8]) <= 1e-6
+
+
+@pytest.mark.parametrize("cfg", [SMALL[0], SMALL[1], SMALL[3], SMALL[6]], ids=lambda c: c.name)
+def test_token_permutation_equivariance_bitwise(B, cfg):
+    """The block is defined per token (Section 2.1): shuffling the batch shuffles
+    the outputs and nothing else.  Every output row is a fixed-order sum over
+    the hidden / FFN dimension and over the k slots, so the bits must agree
+    wherever a token lands in its bucket."""
+    L = make_layer(cfg)
+    order = np.random.Generator(np.random.PCG64(31)).permutation(cfg.T)
+    a = _layer_gpu(B, cfg, L)
+    b = _layer_gpu(B, cfg, dict(L, X=np.ascontiguousarray(L["X"][order])))
+    assert np.array_equal(b["topk_idx"], a["topk_idx"][order])
+    assert np.array_equal(b["topk_w"], a["topk_w"][order])
+    assert np.array_equal(b["out"], a["out"][order])
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_down_projection_scales_linearly(B, layout):
+    """Doubling every down projection (exact in bf16) doubles the block output
+    exactly: the expert output is linear in Wd and the gate never sees it."""
+    cfg = SMALL[1]
+    L = make_layer(cfg)
+    base = _layer_gpu(B, cfg, L, layout=layout)
+    Wd = L["Wd"]
+    Wd2 = np.where((Wd & 0x7F80) == 0, Wd, Wd + np.uint16(1 << 7)).astype(np.uint16)   # exponent + 1, zeros stay
+    assert np.array_equal(O.widen(Wd2), 2.0 * O.widen(L["Wd"]))
+    twice = _layer_gpu(B, cfg, dict(L, Wd=Wd2), layout=layout)
+    assert np.array_equal(twice["topk_idx"], base["topk_idx"])
+    assert np.array_equal(twice["out"], 2.0 * base["out"])
