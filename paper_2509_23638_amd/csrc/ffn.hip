@@ -935,46 +935,67 @@ __global__ __launch_bounds__(kThreads) void ffn_f32_kernel(F32Args a, ExpertTabl
 
 }  // namespace
 
-// Down projection at decode sizes (block variant 0):
-//   0: the stream kernel, 128 rows per workgroup
-//   1: the four-wave split-K kernel (32 rows per workgroup, activations straight
-//      from L2): best when very few experts are active, it keeps the chip full
-//   2: the stream kernel with the contraction halved inside each wave (64 rows
-//      per workgroup)
-// MOE_TUNE_DOWN=lds|splitk|halves overrides the choice (for measurements).
-int block_variant(const moe_shape& s);
-int down_variant(const moe_shape& s) {
-  static const char* env = getenv("MOE_TUNE_DOWN");
-  const bool halves_ok = (s.F / kChunk) % 2 == 0;
-  if (env && env[0] == 'l') return 0;
-  if (env && env[0] == 's') return 1;
-  if (env && env[0] == 'h' && halves_ok) return 2;
-  if (block_variant(s) != 0) return 0;
-  const double rows = (double)s.T * s.k / s.E;
-  if (rows <= 24.0 && (s.S == 0 || s.T <= 32)) return (rows <= 4.0 || !halves_ok) ? 1 : 2;
-  return 0;
-}
-
-// Which stream-kernel variant serves a shape:
-//   0: 64-row passes, one weight tile per wave and matrix (decode)
-//   1: 128-row passes, so an expert's weights are still read once when it is
-//      expected to see more than 48 rows
-//   2: 128-row passes and two weight tiles per wave and matrix: every
-//      activation fragment read from LDS feeds four MFMAs
-//   3: the tiled kernel (256 x 256 blocks, both operands through LDS) once the
-//      batch is compute-heavy (prefill)
-// MOE_TUNE_BLOCK=0..3 overrides the choice (for measurements).
-int block_variant(const moe_shape& s) {
-  static const char* env = getenv("MOE_TUNE_BLOCK");
-  if (env && env[0] >= '0' && env[0] <= '3') return env[0] - '0';
-  const double rows = (double)s.T * s.k / s.E;
-  if (rows > 96.0 || (s.S > 0 && s.T > 256)) return 3;
-  if (rows > 48.0 || (s.S > 0 && s.T > 128)) return 1;
-  return 0;
-}
+// Which kernel serves a phase.  Gate/up and down choose separately:
+//   kStream64   the stream kernel, 64-row passes, one weight tile per wave and matrix
+//   kStream128  the stream kernel, 128-row passes (an expert with up to 128
+//               rows still has its weights read once)
+//   kStream128x2 128-row passes and two weight tiles per wave and matrix
+//   kTile       the tiled kernel (persistent, both operands through LDS)
+//   kSplitK     down only: four waves split the contraction (32 rows per
+//               workgroup, activations straight from L2): keeps the chip full
+//               when very few experts are active
+//   kHalves     down only: the stream kernel with the contraction halved
+//               inside each wave (64 rows per workgroup)
+// The tiled kernel is not only the many-rows form: its deep direct-to-LDS
+// fetch ring streams long weight rows faster than the register-staged stream
+// kernel does (5.6 against 5.3 TB/s on a Mixtral-shaped gate/up at 64 tokens),
+// so it also takes the gate/up phase of wide layers at decode sizes, and both
+// phases from about 24 rows per expert on.
+// MOE_TUNE_BLOCK=0..3 forces stream64 / stream128 / stream128x2 / tile for both
+// phases, MOE_TUNE_GU=0..3 for gate/up only, MOE_TUNE_DOWN=lds|splitk|halves|tile
+// for down only (measurement aids).
+enum Variant { kStream64 = 0, kStream128 = 1, kStream128x2 = 2, kTile = 3, kSplitK = 4, kHalves = 5 };
 
 // The tiled kernel walks the contraction in steps of 64 and owns 64 / 128 rows.
 bool tile_kernel_fits(const moe_shape& s) { return s.H % 128 == 0 && s.F % 64 == 0; }
+
+static int forced_block() {
+  static const char* env = getenv("MOE_TUNE_BLOCK");
+  return (env && env[0] >= '0' && env[0] <= '3') ? env[0] - '0' : -1;
+}
+
+static Variant rows_rule(const moe_shape& s) {
+  const double rows = (double)s.T * s.k / s.E;   // expected rows per routed expert
+  if (tile_kernel_fits(s) && (rows >= 24.0 || (s.S > 0 && s.T > 256))) return kTile;
+  if (rows > 48.0 || (s.S > 0 && s.T > 128)) return kStream128;
+  return kStream64;
+}
+
+Variant gate_up_variant(const moe_shape& s, int n_groups) {
+  static const char* env = getenv("MOE_TUNE_GU");
+  if (env && env[0] >= '0' && env[0] <= '3') return (Variant)(env[0] - '0');
+  if (forced_block() >= 0) return (Variant)forced_block();
+  const Variant v = rows_rule(s);
+  // long rows and enough (expert, slab) items to deal every compute unit several
+  if (v != kTile && tile_kernel_fits(s) && s.H >= 4096 && (long)n_groups * (s.F / 64) >= 4 * 256)
+    return kTile;
+  return v;
+}
+
+Variant down_variant(const moe_shape& s) {
+  static const char* env = getenv("MOE_TUNE_DOWN");
+  const bool halves_ok = (s.F / kChunk) % 2 == 0;
+  if (env && env[0] == 'l') return kStream64;
+  if (env && env[0] == 's') return kSplitK;
+  if (env && env[0] == 'h' && halves_ok) return kHalves;
+  if (env && env[0] == 't' && tile_kernel_fits(s)) return kTile;
+  if (forced_block() >= 0) return (Variant)forced_block();
+  const Variant v = rows_rule(s);
+  if (v != kStream64) return v;
+  const double rows = (double)s.T * s.k / s.E;
+  if (s.S == 0 || s.T <= 32) return (rows <= 4.0 || !halves_ok) ? kSplitK : kHalves;
+  return kStream64;
+}
 
 // Phase 1 (gate and up projections, SiLU gate) for the experts in `groups`.
 moe_status launch_ffn_gate_up(const moe_shape& s, const void* X, const int32_t* perm,
@@ -987,13 +1008,13 @@ moe_status launch_ffn_gate_up(const moe_shape& s, const void* X, const int32_t* 
   if (s.dtype == MOE_BF16) {
     FfnArgs gu{static_cast<const uint16_t*>(X), perm, offset, h, s.T, s.k, s.E, A, s.H, s.F,
                s.weight_layout == MOE_TILED};
-    const int v = block_variant(s);
-    if (v == 3 && tile_kernel_fits(s)) {
+    const Variant v = gate_up_variant(s, groups.n);
+    if (v == kTile && tile_kernel_fits(s)) {
       return launch_tile<kGateUp>(s, gu, tab, groups, scratch.plan, stream);
-    } else if (v >= 2 && s.F % (kWaves * 32) == 0) {
+    } else if (v == kStream128x2 && s.F % (kWaves * 32) == 0) {
       hipLaunchKernelGGL((ffn_stream_kernel<kGateUp, 8, 2>), dim3(s.F / (kWaves * 32), groups.n, (s.T + 127) / 128),
                          dim3(kThreads), 0, stream, gu, tab, groups);
-    } else if (v >= 1) {
+    } else if (v != kStream64) {
       hipLaunchKernelGGL((ffn_stream_kernel<kGateUp, 8, 1>), dim3(s.F / (kWaves * 16), groups.n, (s.T + 127) / 128),
                          dim3(kThreads), 0, stream, gu, tab, groups);
     } else {
@@ -1021,19 +1042,20 @@ moe_status launch_ffn_down(const moe_shape& s, const FfnScratch& scratch, const 
   if (s.dtype == MOE_BF16) {
     FfnArgs dn{static_cast<const uint16_t*>(h), perm, offset, Y, s.T, s.k, s.E, A, s.F, s.H,
                s.weight_layout == MOE_TILED};
-    if (block_variant(s) == 3 && tile_kernel_fits(s)) {
+    const Variant v = down_variant(s);
+    if (v == kTile && tile_kernel_fits(s)) {
       return launch_tile<kDown>(s, dn, tab, groups, scratch.plan, stream);
-    } else if (down_variant(s) == 2) {
+    } else if (v == kHalves) {
       hipLaunchKernelGGL((ffn_stream_kernel<kDownHalves, 4, 1>), dim3(s.H / (kWaves * 16), groups.n, (s.T + 63) / 64),
                          dim3(kThreads), 0, stream, dn, tab, groups);
-    } else if (down_variant(s) == 1) {
+    } else if (v == kSplitK) {
       const int tok_blocks = (s.T + kSplitTok - 1) / kSplitTok;
       hipLaunchKernelGGL(ffn_down_splitk_kernel, dim3(s.H / kSplitRows, groups.n, tok_blocks),
                          dim3(kThreads), 0, stream, dn, tab, groups);
-    } else if (block_variant(s) >= 2 && s.H % (kWaves * 64) == 0) {
+    } else if (v == kStream128x2 && s.H % (kWaves * 64) == 0) {
       hipLaunchKernelGGL((ffn_stream_kernel<kDown, 8, 2>), dim3(s.H / (kWaves * 64), groups.n, (s.T + 127) / 128),
                          dim3(kThreads), 0, stream, dn, tab, groups);
-    } else if (block_variant(s) >= 1) {
+    } else if (v != kStream64) {
       hipLaunchKernelGGL((ffn_stream_kernel<kDown, 8, 1>), dim3(s.H / (kWaves * 32), groups.n, (s.T + 127) / 128),
                          dim3(kThreads), 0, stream, dn, tab, groups);
     } else {
