@@ -514,17 +514,21 @@ __device__ __forceinline__ void tile_sources(const FfnArgs& a, const ExpertTable
   for (int q = 0; q < kFetchPerWave; ++q) asm volatile("" : "+v"(src[q]));
 }
 
-// Issue this wave's twelve fetches of stage st into ring buffer st % 3.  A
-// source pointer advances 64 elements along its row per stage, or two KiB
-// tiles for tiled weights.
+// Issue this wave's fetches of stage st into ring buffer st % 3: the first NTOK
+// of its eight token fetches (token blocks 0 .. 2 NTOK - 1 of the sixteen) and
+// its four weight fetches.  A source pointer advances 64 elements along its row
+// per stage, or two KiB tiles for tiled weights.
+template <int NTOK>
 __device__ __forceinline__ void tile_fetch(const uint16_t* const (&src)[kFetchPerWave], int st,
                                            int w_adv, int wave, unsigned char* ring) {
   unsigned char* base = ring + (st % kTileStages) * kTileStage;
 #pragma unroll
-  for (int q = 0; q < kFetchPerWave; ++q)
+  for (int q = 0; q < kFetchPerWave; ++q) {
+    if (q >= NTOK && q < 8) continue;
     __builtin_amdgcn_global_load_lds(
         (const __attribute__((address_space(1))) void*)(src[q] + (size_t)st * (q >= 8 ? w_adv : kTileK)),
         (__attribute__((address_space(3))) void*)(base + (wave + 4 * q) * kFragBytes), 16, 0, 0);
+  }
 }
 
 // One item.  On entry the fetches of its stages 0 and 1 are in flight (issued
@@ -575,13 +579,17 @@ __device__ __forceinline__ void ffn_tile_block(const FfnArgs& a, const ExpertTab
     // barrier has to order is covered by hand: the vmcnt wait above it (this
     // wave's direct-to-LDS fetches of stage st have been written), and program
     // order (a wave's LDS reads of stage st-1 fed MFMAs it has already issued).
-    if (st + 1 < ns) asm volatile("s_waitcnt vmcnt(12)\n\ts_barrier" ::: "memory");
+    // (Stages 2.. of an item fetch only the token blocks it multiplies, NJ + 4
+    // fetches per wave; the two stages an item inherits were fetched in full.
+    // Waiting for "all but the newest NJ + 4" is exact or conservative in both
+    // cases, because loads complete in order.)
+    if (st + 1 < ns) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(NJ + 4) : "memory");
     else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
     // the next item's row look-ups: issued early (ahead of this stage's fetches, so
     // that the in-order wait above never has to wait for more than one stage of
     // fetches), needed only after the last stage
     if (st == 1 && has_next) tile_rows<MODE>(a, nxt, lane, wave, next_ids);
-    if (st + 2 < ns) tile_fetch(src, st + 2, w_adv, wave, ring);   // into the buffer stage st-1 used
+    if (st + 2 < ns) tile_fetch<NJ>(src, st + 2, w_adv, wave, ring);   // into the buffer stage st-1 used
     const unsigned char* base = ring + (st % kTileStages) * kTileStage;
     // LDS reads of both k-steps are issued up front, in order; the MFMAs of the
     // first k-step only wait for its own operands (LDS returns in order), so the
@@ -656,8 +664,8 @@ __device__ __forceinline__ void ffn_tile_block(const FfnArgs& a, const ExpertTab
     if (ns < 2) tile_rows<MODE>(a, nxt, lane, wave, next_ids);
     tile_sources<MODE>(a, tab, nxt, next_ids, lane, wave, next_src);
     asm volatile("s_barrier" ::: "memory");
-    tile_fetch(next_src, 0, w_adv, wave, ring);
-    if (ns > 1) tile_fetch(next_src, 1, w_adv, wave, ring);
+    tile_fetch<8>(next_src, 0, w_adv, wave, ring);   // in full: the next item's size is not a constant here
+    if (ns > 1) tile_fetch<8>(next_src, 1, w_adv, wave, ring);
     epilogue();
 #pragma unroll
     for (int q = 0; q < kFetchPerWave; ++q) src[q] = next_src[q];
@@ -694,8 +702,8 @@ __global__ __launch_bounds__(kThreads, 1) void ffn_tile_kernel(FfnArgs a, Expert
     int rows[8];
     tile_rows<MODE>(a, it, lane, wave, rows);
     tile_sources<MODE>(a, tab, it, rows, lane, wave, src);
-    tile_fetch(src, 0, w_adv, wave, ring);
-    if (a.K / kTileK > 1) tile_fetch(src, 1, w_adv, wave, ring);
+    tile_fetch<8>(src, 0, w_adv, wave, ring);
+    if (a.K / kTileK > 1) tile_fetch<8>(src, 1, w_adv, wave, ring);
   }
   while (true) {
     const bool has_next = lo + local + stride < hi;
