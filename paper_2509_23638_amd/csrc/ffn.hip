@@ -957,8 +957,9 @@ __global__ __launch_bounds__(kThreads) void ffn_f32_kernel(F32Args a, ExpertTabl
 // The tiled kernel is not only the many-rows form: its deep direct-to-LDS
 // fetch ring streams long weight rows faster than the register-staged stream
 // kernel does (5.6 against 5.3 TB/s on a Mixtral-shaped gate/up at 64 tokens),
-// so it also takes the gate/up phase of wide layers at decode sizes, and both
-// phases from about 24 rows per expert on.
+// so it also takes the gate/up phase of wide experts at decode sizes (their
+// many slabs balance over the persistent workgroups), and both phases from
+// about 24 rows per expert on.
 // MOE_TUNE_BLOCK=0..3 forces stream64 / stream128 / stream128x2 / tile for both
 // phases, MOE_TUNE_GU=0..3 for gate/up only, MOE_TUNE_DOWN=lds|splitk|halves|tile
 // for down only (measurement aids).
@@ -984,8 +985,9 @@ Variant gate_up_variant(const moe_shape& s, int n_groups) {
   if (env && env[0] >= '0' && env[0] <= '3') return (Variant)(env[0] - '0');
   if (forced_block() >= 0) return (Variant)forced_block();
   const Variant v = rows_rule(s);
-  // long rows and enough (expert, slab) items to deal every compute unit several
-  if (v != kTile && tile_kernel_fits(s) && s.H >= 4096 && (long)n_groups * (s.F / 64) >= 4 * 256)
+  // wide experts: many slabs per expert, so the persistent workgroups get even
+  // shares whatever number of experts turns out to be active
+  if (v != kTile && tile_kernel_fits(s) && s.F / 64 >= 64 && (long)n_groups * (s.F / 64) >= 2 * 256)
     return kTile;
   return v;
 }
