@@ -406,8 +406,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, T, args.layout)),
-                     "kernel": ("ffn_tile_kernel<gate/up>" if args.workload == "c4_dsv2lite_prefill"
-                                else "ffn_stream_kernel<gate/up>"), "kernel_ms": gu_ms,
+                     "kernel": B.moe_ffn_kernel_name(sh, 0, cfg.E + cfg.S), "kernel_ms": gu_ms,
                      "algorithmic_bytes": gu_bytes},
         "phases_ms": {k: ph[k] / max(1, ph["n_layers"]) for k in
                       ("route_ms", "permute_ms", "gate_up_ms", "down_ms", "combine_ms")},

@@ -305,6 +305,11 @@ moe_status moe_phase_times_get(moe_ctx* ctx, moe_phase_times* out, int32_t reset
 moe_status moe_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
 moe_status moe_probe_read(const void* src, size_t bytes, void* sink4, void* stream);
 
+/* Which kernel the grouped FFN launches for a shape (measurement aid for
+ * reports): phase 0 = gate/up, 1 = down; n_groups = experts listed in the call
+ * (routed + shared).  Returns a static string, "" for an invalid request. */
+const char* moe_ffn_kernel_name(const moe_shape* shape, int32_t phase, int32_t n_groups);
+
 /* Views into a workspace after moe_layer_forward (device pointers into
  * `workspace`; for tests and harnesses).  Any output pointer may be NULL. */
 moe_status moe_workspace_views(const moe_shape* shape, void* workspace,

@@ -100,6 +100,8 @@ _P = C.c_void_p
 _SH = C.POINTER(moe_shape)
 _lib.moe_version.restype = C.c_char_p
 _lib.moe_last_error.restype = C.c_char_p
+_lib.moe_ffn_kernel_name.restype = C.c_char_p
+_lib.moe_ffn_kernel_name.argtypes = [_SH, C.c_int32, C.c_int32]
 _lib.moe_workspace_bytes.restype = C.c_size_t
 _lib.moe_workspace_bytes.argtypes = [_SH]
 _lib.moe_route.argtypes = [_SH, _P, _P, _P, _P, _P, _P, _P, _P]
@@ -138,12 +140,17 @@ EXPORTS = ["moe_version", "moe_last_error", "moe_workspace_bytes", "moe_route", 
            "moe_stream_totals_get", "moe_workspace_views", "moe_phase_timing",
            "moe_phase_times_get", "moe_probe_copy", "moe_probe_read", "moe_rmsnorm",
            "moe_set_option", "moe_pack_weights",
-           "moe_counter_add", "moe_hot_table", "moe_predict_counts", "moe_presched"]
+           "moe_counter_add", "moe_hot_table", "moe_predict_counts", "moe_presched",
+           "moe_ffn_kernel_name"]
 
 
 def _check(st: int):
     if st != 0:
         raise MoEError(st, _lib.moe_last_error().decode())
+
+
+def moe_ffn_kernel_name(shape, phase: int, n_groups: int) -> str:
+    return _lib.moe_ffn_kernel_name(C.byref(shape), phase, n_groups).decode()
 
 
 def moe_version() -> str:

@@ -1106,6 +1106,18 @@ moe_status launch_grouped_ffn(const moe_shape& s, const void* X, const int32_t* 
                           nullptr);
 }
 
+const char* ffn_kernel_name(const moe_shape& s, int phase, int n_groups) {
+  if (s.dtype != MOE_BF16) return phase == 0 ? "ffn_f32_kernel<gate/up>" : "ffn_f32_kernel<down>";
+  const Variant v = phase == 0 ? gate_up_variant(s, n_groups) : down_variant(s);
+  switch (v) {
+    case kTile: return phase == 0 ? "ffn_tile_kernel<gate/up>" : "ffn_tile_kernel<down>";
+    case kSplitK: return "ffn_down_splitk_kernel";
+    case kHalves: return "ffn_stream_kernel<down, halved contraction>";
+    case kStream64: return phase == 0 ? "ffn_stream_kernel<gate/up, 64 rows>" : "ffn_stream_kernel<down, 64 rows>";
+    default: return phase == 0 ? "ffn_stream_kernel<gate/up, 128 rows>" : "ffn_stream_kernel<down, 128 rows>";
+  }
+}
+
 }  // namespace moe
 
 extern "C" moe_status moe_grouped_ffn(const moe_shape* shape, const void* X, const int32_t* perm,
@@ -1137,4 +1149,9 @@ extern "C" moe_status moe_grouped_ffn(const moe_shape* shape, const void* X, con
                                 reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + L.plan)};
   return moe::launch_grouped_ffn(*shape, X, perm, offset, tab, groups, Y, scratch,
                                  static_cast<hipStream_t>(stream));
+}
+
+extern "C" const char* moe_ffn_kernel_name(const moe_shape* shape, int32_t phase, int32_t n_groups) {
+  if (moe::check_shape(shape, "moe_ffn_kernel_name") != MOE_OK || phase < 0 || phase > 1) return "";
+  return moe::ffn_kernel_name(*shape, phase, n_groups);
 }
