@@ -38,7 +38,7 @@ static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 
 // Workspace carve-up (all offsets 256-byte aligned).
 struct WorkspaceLayout {
-  size_t topk_idx, topk_w, count, offset, perm, inv_perm, plan, logits, h, y, total;
+  size_t topk_idx, topk_w, count, offset, perm, inv_perm, logits, h, y, total;
 };
 WorkspaceLayout workspace_layout(const moe_shape& s);
 
@@ -58,13 +58,10 @@ struct GroupList {
   uint8_t id[MOE_MAX_GROUPS];
 };
 
-// Scratch of the grouped FFN inside a workspace: the intermediate h and the
-// row-block plan of the tiled (prefill) kernels.
+// Scratch of the grouped FFN inside a workspace: the intermediate h.
 struct FfnScratch {
   void* h;
-  int32_t* plan;
 };
-size_t plan_bytes(const moe_shape& s);
 
 // internal launchers (each enqueues on `stream`, returns a status)
 moe_status launch_route(const moe_shape& s, const void* X, const void* Wr, const float* bias,

@@ -38,12 +38,6 @@ moe_status check_shape(const moe_shape* s, const char* who) {
   return MOE_OK;
 }
 
-size_t plan_bytes(const moe_shape& s) {
-  // 1 + 3 ints per 256-row block; at most rows/256 + one partial block per group
-  const size_t blocks = ((size_t)s.T * s.k + (size_t)s.S * s.T) / 256 + s.E + s.S + 1;
-  return (1 + 3 * blocks) * sizeof(int32_t);
-}
-
 WorkspaceLayout workspace_layout(const moe_shape& s) {
   WorkspaceLayout L;
   const size_t A = (size_t)s.T * s.k, rows = A + (size_t)s.S * s.T;
@@ -55,7 +49,6 @@ WorkspaceLayout workspace_layout(const moe_shape& s) {
   L.offset = take((size_t)(s.E + 1) * 4);
   L.perm = take(A * 4);
   L.inv_perm = take(A * 4);
-  L.plan = take(plan_bytes(s));
   L.logits = take((size_t)s.T * s.E * sizeof(double));
   L.h = take(rows * s.F * elem_size(s));
   L.y = take(rows * s.H * 4);

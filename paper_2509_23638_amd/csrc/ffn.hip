@@ -356,45 +356,36 @@ constexpr int kTileStages = 3;
 constexpr int kTileLds = kTileStage * kTileStages;
 constexpr int kFetchPerWave = 12;                 // 48 fetches per stage over 4 waves
 
-// plan[0] = number of row blocks; then (group index, first row, end row) per block
-__global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict__ offset, int T,
-                                                       int E, int A, GroupList groups,
-                                                       int32_t* __restrict__ plan) {
-  __shared__ int s_begin[MOE_MAX_GROUPS], s_rows[MOE_MAX_GROUPS], s_first[MOE_MAX_GROUPS + 1];
+// The list of 256-row blocks of the experts in a launch.  Every workgroup
+// derives it on its own from the bucket offsets (at most 136 groups: cheaper
+// than a launch of its own and a round trip through memory): per group its
+// first row, its row count and the index of its first block.
+struct TilePlan {
+  int begin[MOE_MAX_GROUPS], rows[MOE_MAX_GROUPS], first[MOE_MAX_GROUPS + 1];
+};
+
+__device__ __forceinline__ void tile_plan_build(TilePlan& pl, const FfnArgs& a, const GroupList& groups) {
   const int i = threadIdx.x;
   if (i < groups.n) {
     const int e = groups.id[i];
     int b, n;
-    if (e < E) {
-      b = offset[e];
-      n = offset[e + 1] - b;
+    if (e < a.E) {
+      b = a.offset[e];
+      n = a.offset[e + 1] - b;
     } else {
-      b = A + (e - E) * T;
-      n = T;
+      b = a.A + (e - a.E) * a.T;
+      n = a.T;
     }
-    s_begin[i] = b;
-    s_rows[i] = n;
+    pl.begin[i] = b;
+    pl.rows[i] = n;
   }
   __syncthreads();
-  if (i == 0) {
+  if (i <= groups.n) {
     int run = 0;
-    for (int q = 0; q < groups.n; ++q) {
-      s_first[q] = run;
-      run += (s_rows[q] + kTileRows - 1) / kTileRows;
-    }
-    s_first[groups.n] = run;
-    plan[0] = run;
+    for (int q = 0; q < i; ++q) run += (pl.rows[q] + kTileRows - 1) / kTileRows;
+    pl.first[i] = run;
   }
   __syncthreads();
-  if (i < groups.n) {
-    const int nb = s_first[i + 1] - s_first[i];
-    for (int q = 0; q < nb; ++q) {
-      int32_t* p = plan + 1 + 3 * (s_first[i] + q);
-      p[0] = i;
-      p[1] = s_begin[i] + q * kTileRows;
-      p[2] = s_begin[i] + s_rows[i];
-    }
-  }
 }
 
 // Placement of a 16-row x 64-k operand block in LDS (2 KiB = two fetches).
@@ -431,14 +422,27 @@ struct TileItem {
   int e, r0, row_end, slab;
 };
 
-__device__ __forceinline__ TileItem tile_item(const GroupList& groups, const int32_t* plan, int item,
+__device__ __forceinline__ TileItem tile_item(const GroupList& groups, const TilePlan& pl, int item,
                                               int slabs) {
   const int blk = item / slabs;
+  // the one group whose block range holds blk (groups without rows have an
+  // empty range): every lane tests a group, a ballot names the hit
+  const int lane = threadIdx.x & (MOE_WAVE - 1);
+  int g = 0;
+  for (int base = 0; base < groups.n; base += MOE_WAVE) {
+    const int cand = min(base + lane, groups.n - 1);
+    const bool hit = base + lane < groups.n && pl.first[cand] <= blk && blk < pl.first[cand + 1];
+    const unsigned long long m = __builtin_amdgcn_ballot_w64(hit);
+    if (m) {
+      g = base + __ffsll(m) - 1;
+      break;
+    }
+  }
   TileItem it;
   it.slab = item - blk * slabs;
-  it.e = groups.id[plan[1 + 3 * blk]];
-  it.r0 = plan[2 + 3 * blk];
-  it.row_end = plan[3 + 3 * blk];
+  it.e = groups.id[g];
+  it.r0 = pl.begin[g] + (blk - pl.first[g]) * kTileRows;
+  it.row_end = pl.begin[g] + pl.rows[g];
   return it;
 }
 
@@ -683,11 +687,12 @@ __device__ __forceinline__ void ffn_tile_block(const FfnArgs& a, const ExpertTab
 // weights) are in flight together.
 template <int MODE>
 __global__ __launch_bounds__(kThreads, 1) void ffn_tile_kernel(FfnArgs a, ExpertTable tab,
-                                                               GroupList groups,
-                                                               const int32_t* __restrict__ plan) {
+                                                               GroupList groups) {
   extern __shared__ __attribute__((aligned(16))) unsigned char ring[];
+  __shared__ TilePlan plan;
+  tile_plan_build(plan, a, groups);
   const int slabs = a.N / (MODE == kGateUp ? 64 : 128);
-  const int total = plan[0] * slabs;
+  const int total = plan.first[groups.n] * slabs;
   const int per_xcd = (total + 7) / 8;
   const int xcd = blockIdx.x & 7, stride = gridDim.x >> 3;   // grid is a multiple of 8
   int local = blockIdx.x >> 3;
@@ -728,15 +733,13 @@ int max_row_blocks(const moe_shape& s) {
 
 template <int MODE>
 moe_status launch_tile(const moe_shape& s, const FfnArgs& args, const ExpertTable& tab,
-                       const GroupList& groups, int32_t* plan, hipStream_t stream) {
+                       const GroupList& groups, hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
     MOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_tile_kernel<MODE>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kTileLds));
     attr_set = true;
   }
-  hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, stream, args.offset, s.T, s.E, args.A,
-                     groups, plan);
   const int slabs = MODE == kGateUp ? s.F / 64 : s.H / 128;
   // one persistent workgroup per compute unit, never more than there can be items
   static int n_cu = 0;
@@ -747,7 +750,7 @@ moe_status launch_tile(const moe_shape& s, const FfnArgs& args, const ExpertTabl
   }
   const int grid = (std::min(slabs * max_row_blocks(s), n_cu) + 7) / 8 * 8;
   hipLaunchKernelGGL((ffn_tile_kernel<MODE>), dim3(grid), dim3(kThreads), kTileLds, stream, args,
-                     tab, groups, plan);
+                     tab, groups);
   MOE_HIP(hipGetLastError());
   return MOE_OK;
 }
@@ -1020,7 +1023,7 @@ moe_status launch_ffn_gate_up(const moe_shape& s, const void* X, const int32_t* 
                s.weight_layout == MOE_TILED};
     const Variant v = gate_up_variant(s, groups.n);
     if (v == kTile && tile_kernel_fits(s)) {
-      return launch_tile<kGateUp>(s, gu, tab, groups, scratch.plan, stream);
+      return launch_tile<kGateUp>(s, gu, tab, groups, stream);
     } else if (v == kStream128x2 && s.F % (kWaves * 32) == 0) {
       hipLaunchKernelGGL((ffn_stream_kernel<kGateUp, 8, 2>), dim3(s.F / (kWaves * 32), groups.n, (s.T + 127) / 128),
                          dim3(kThreads), 0, stream, gu, tab, groups);
@@ -1054,7 +1057,7 @@ moe_status launch_ffn_down(const moe_shape& s, const FfnScratch& scratch, const 
                s.weight_layout == MOE_TILED};
     const Variant v = down_variant(s);
     if (v == kTile && tile_kernel_fits(s)) {
-      return launch_tile<kDown>(s, dn, tab, groups, scratch.plan, stream);
+      return launch_tile<kDown>(s, dn, tab, groups, stream);
     } else if (v == kHalves) {
       hipLaunchKernelGGL((ffn_stream_kernel<kDownHalves, 4, 1>), dim3(s.H / (kWaves * 16), groups.n, (s.T + 63) / 64),
                          dim3(kThreads), 0, stream, dn, tab, groups);
@@ -1145,8 +1148,7 @@ extern "C" moe_status moe_grouped_ffn(const moe_shape* shape, const void* X, con
     }
   }
   const moe::WorkspaceLayout L = moe::workspace_layout(*shape);
-  const moe::FfnScratch scratch{static_cast<char*>(workspace) + L.h,
-                                reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + L.plan)};
+  const moe::FfnScratch scratch{static_cast<char*>(workspace) + L.h};
   return moe::launch_grouped_ffn(*shape, X, perm, offset, tab, groups, Y, scratch,
                                  static_cast<hipStream_t>(stream));
 }

@@ -341,7 +341,7 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
   int32_t* offset = reinterpret_cast<int32_t*>(w + L.offset);
   int32_t* perm = reinterpret_cast<int32_t*>(w + L.perm);
   int32_t* inv_perm = reinterpret_cast<int32_t*>(w + L.inv_perm);
-  const FfnScratch h{w + L.h, reinterpret_cast<int32_t*>(w + L.plan)};
+  const FfnScratch h{w + L.h};
   float* Y = reinterpret_cast<float*>(w + L.y);
   const size_t mb = (size_t)s.H * s.F * elem_size(s);
 
