@@ -950,7 +950,6 @@ __global__ __launch_bounds__(kThreads) void ffn_f32_kernel(F32Args a, ExpertTabl
 //   kStream64   the stream kernel, 64-row passes, one weight tile per wave and matrix
 //   kStream128  the stream kernel, 128-row passes (an expert with up to 128
 //               rows still has its weights read once)
-//   kStream128x2 128-row passes and two weight tiles per wave and matrix
 //   kTile       the tiled kernel (persistent, both operands through LDS)
 //   kSplitK     down only: four waves split the contraction (32 rows per
 //               workgroup, activations straight from L2): keeps the chip full
@@ -963,17 +962,17 @@ __global__ __launch_bounds__(kThreads) void ffn_f32_kernel(F32Args a, ExpertTabl
 // so it also takes the gate/up phase of wide experts at decode sizes (their
 // many slabs balance over the persistent workgroups), and both phases from
 // about 24 rows per expert on.
-// MOE_TUNE_BLOCK=0..3 forces stream64 / stream128 / stream128x2 / tile for both
-// phases, MOE_TUNE_GU=0..3 for gate/up only, MOE_TUNE_DOWN=lds|splitk|halves|tile
+// MOE_TUNE_BLOCK=0|1|3 forces stream64 / stream128 / tile for both phases,
+// MOE_TUNE_GU=0|1|3 for gate/up only, MOE_TUNE_DOWN=lds|splitk|halves|tile
 // for down only (measurement aids).
-enum Variant { kStream64 = 0, kStream128 = 1, kStream128x2 = 2, kTile = 3, kSplitK = 4, kHalves = 5 };
+enum Variant { kStream64 = 0, kStream128 = 1, kTile = 3, kSplitK = 4, kHalves = 5 };
 
 // The tiled kernel walks the contraction in steps of 64 and owns 64 / 128 rows.
 bool tile_kernel_fits(const moe_shape& s) { return s.H % 128 == 0 && s.F % 64 == 0; }
 
 static int forced_block() {
   static const char* env = getenv("MOE_TUNE_BLOCK");
-  return (env && env[0] >= '0' && env[0] <= '3') ? env[0] - '0' : -1;
+  return (env && (env[0] == '0' || env[0] == '1' || env[0] == '3')) ? env[0] - '0' : -1;
 }
 
 static Variant rows_rule(const moe_shape& s) {
@@ -985,7 +984,7 @@ static Variant rows_rule(const moe_shape& s) {
 
 Variant gate_up_variant(const moe_shape& s, int n_groups) {
   static const char* env = getenv("MOE_TUNE_GU");
-  if (env && env[0] >= '0' && env[0] <= '3') return (Variant)(env[0] - '0');
+  if (env && (env[0] == '0' || env[0] == '1' || env[0] == '3')) return (Variant)(env[0] - '0');
   if (forced_block() >= 0) return (Variant)forced_block();
   const Variant v = rows_rule(s);
   // wide experts: many slabs per expert, so the persistent workgroups get even
@@ -1024,9 +1023,6 @@ moe_status launch_ffn_gate_up(const moe_shape& s, const void* X, const int32_t* 
     const Variant v = gate_up_variant(s, groups.n);
     if (v == kTile && tile_kernel_fits(s)) {
       return launch_tile<kGateUp>(s, gu, tab, groups, stream);
-    } else if (v == kStream128x2 && s.F % (kWaves * 32) == 0) {
-      hipLaunchKernelGGL((ffn_stream_kernel<kGateUp, 8, 2>), dim3(s.F / (kWaves * 32), groups.n, (s.T + 127) / 128),
-                         dim3(kThreads), 0, stream, gu, tab, groups);
     } else if (v != kStream64) {
       hipLaunchKernelGGL((ffn_stream_kernel<kGateUp, 8, 1>), dim3(s.F / (kWaves * 16), groups.n, (s.T + 127) / 128),
                          dim3(kThreads), 0, stream, gu, tab, groups);
@@ -1064,9 +1060,6 @@ moe_status launch_ffn_down(const moe_shape& s, const FfnScratch& scratch, const 
     } else if (v == kSplitK) {
       const int tok_blocks = (s.T + kSplitTok - 1) / kSplitTok;
       hipLaunchKernelGGL(ffn_down_splitk_kernel, dim3(s.H / kSplitRows, groups.n, tok_blocks),
-                         dim3(kThreads), 0, stream, dn, tab, groups);
-    } else if (v == kStream128x2 && s.H % (kWaves * 64) == 0) {
-      hipLaunchKernelGGL((ffn_stream_kernel<kDown, 8, 2>), dim3(s.H / (kWaves * 64), groups.n, (s.T + 127) / 128),
                          dim3(kThreads), 0, stream, dn, tab, groups);
     } else if (v != kStream64) {
       hipLaunchKernelGGL((ffn_stream_kernel<kDown, 8, 1>), dim3(s.H / (kWaves * 32), groups.n, (s.T + 127) / 128),

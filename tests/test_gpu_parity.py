@@ -72,6 +72,12 @@ SMALL = [
     _small("s_bf16_route_deep", T=20, E=60, k=4, H=4224, F=128),
     _small("s_bf16_route_mfma_8waves", T=260, E=128, k=8, H=2176, F=128),
     _small("s_bf16_route_fused_long", T=6, E=8, k=2, H=4224, F=128),
+    # FFN kernel choices not reached above: halved-contraction down, 128-row stream passes,
+    # the tiled kernel as the gate/up kernel of wide experts at decode sizes
+    _small("s_bf16_halves", T=40, E=4, k=2, H=256, F=512),
+    _small("s_bf16_128row_passes", T=200, E=60, k=4, S=1, H=128, F=256, bias="zipf", bias_scale=1.1),
+    _small("s_bf16_wide_decode", T=12, E=8, k=2, H=128, F=4096),
+    _small("s_bf16_wide_halves", T=40, E=8, k=2, H=128, F=4096),
 ]
 
 
@@ -411,6 +417,21 @@ def test_layer_forward_c4_prefill_sampled(B, layout):
     assert np.abs(got["topk_w"] - ref["topk_w"]).max() <= 1e-5
     assert row_rel_err(got["out"][sample], ref["out"][sample]) <= TOL["bf16"]
     assert np.array_equal(got["count"], np.bincount(ref["topk_idx"].reshape(-1), minlength=cfg.E))
+
+
+def test_small_configs_reach_every_ffn_kernel(B):
+    """The element-wise parity cases above must between them run every kernel
+    the grouped FFN can choose."""
+    seen = set()
+    for cfg in SMALL:
+        sh = _shape(B, cfg, layout="tiled")
+        for phase in (0, 1):
+            seen.add(B.moe_ffn_kernel_name(sh, phase, cfg.E + cfg.S))
+    want = {"ffn_tile_kernel<gate/up>", "ffn_tile_kernel<down>", "ffn_down_splitk_kernel",
+            "ffn_stream_kernel<down, halved contraction>", "ffn_stream_kernel<gate/up, 64 rows>",
+            "ffn_stream_kernel<down, 64 rows>", "ffn_stream_kernel<gate/up, 128 rows>",
+            "ffn_stream_kernel<down, 128 rows>", "ffn_f32_kernel<gate/up>", "ffn_f32_kernel<down>"}
+    assert want <= seen, want - seen
 
 
 def test_empty_batch_and_errors(B):
