@@ -300,7 +300,7 @@ def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the hot path is a single-GPU "
-              "kernel path; see DESIGN.md for how it would shard). Run with --gpus 1.",
+              "kernel path; sharding by expert is a design note only). Run with --gpus 1.",
               file=sys.stderr)
         sys.exit(2)
 

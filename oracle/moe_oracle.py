@@ -12,7 +12,7 @@ Everything is evaluated token by token in float64 with no intermediate
 rounding, no bucketing and no reordering; numpy's ``@`` (a matrix-vector
 product) is the only library primitive used as a step.
 
-Readings taken where the paper is silent (each also listed in the design doc):
+Readings taken where the paper is silent:
   * selection is on the router logits, ties to the lowest expert index, output
     order = order of selection (descending logit);
   * the k selected weights are renormalised to sum to one;

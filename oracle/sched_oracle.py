@@ -12,8 +12,7 @@ Three pieces, each written out from the paper's equations in its notation:
     recheck (Eq. 4), the prefetch count of Q2 (Eq. 5), the critical-prefetch
     benefit of Q3 (Eq. 6), the no-benefit exit of Q4, with the CPU cost model of Eq. 2.
 
-Readings taken where the paper is silent or at odds with itself (also listed in
-DESIGN.md):
+Readings taken where the paper is silent or at odds with itself:
   * experts with equal token counts are ordered by ascending expert index; in
     the merged list a next-layer expert sorts below a current-layer expert
     with the same count (the current layer's need is certain);
