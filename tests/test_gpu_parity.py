@@ -518,3 +518,34 @@ def test_down_projection_scales_linearly(B, layout):
     twice = _layer_gpu(B, cfg, dict(L, Wd=Wd2), layout=layout)
     assert np.array_equal(twice["topk_idx"], base["topk_idx"])
     assert np.array_equal(twice["out"], 2.0 * base["out"])
+
+
+def test_layer_forward_random_shapes(B):
+    """A seeded sweep over shapes the hand-picked cases may have missed: every
+    case must route exactly and land within the bf16 bar."""
+    r = np.random.Generator(np.random.PCG64(2026))
+    worst = 0.0
+    for i in range(24):
+        E = int(r.choice([1, 2, 3, 4, 8, 20, 60, 64, 128]))
+        k = int(r.integers(1, min(E, 8) + 1))
+        S = int(r.choice([0, 0, 1, 3]))
+        T = int(r.choice([1, 2, 7, 16, 33, 64, 100, 130, 257, 300, 520]))
+        H = int(r.choice([128, 256, 384, 512]))
+        F = int(r.choice([128, 256, 384, 640, 1408, 4096]))
+        if T * (E + S) * F * H > 3e9:
+            F = 128
+        layout = str(r.choice(LAYOUTS))
+        cfg = _small(f"rand{i}", T=T, E=E, k=k, S=S, H=H, F=F, seed=500 + i,
+                     bias=str(r.choice(["none", "normal", "zipf"])), bias_scale=1.0)
+        L = make_layer(cfg)
+        ref = O.moe_layer(L["X"], L["Wr"], L["b"], L["Wg"], L["Wu"], L["Wd"], cfg.k, cfg.S)
+        if E > 1 and O.routing_margins(ref["logits"], cfg.k).min() <= 1e-9:
+            continue
+        got = _layer_gpu(B, cfg, L, layout=layout)
+        what = f"case {i}: {cfg} {layout}"
+        assert np.array_equal(got["topk_idx"], ref["topk_idx"]), what
+        assert np.abs(got["topk_w"] - ref["topk_w"]).max() <= 1e-5, what
+        err = row_rel_err(got["out"], ref["out"])
+        assert err <= TOL["bf16"], what
+        worst = max(worst, err)
+    assert worst > 0.0
