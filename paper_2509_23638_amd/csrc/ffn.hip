@@ -28,6 +28,7 @@
 #include <stdlib.h>
 
 #include <algorithm>
+#include <type_traits>
 
 namespace moe {
 namespace {
@@ -364,6 +365,7 @@ struct TilePlan {
   int begin[MOE_MAX_GROUPS], rows[MOE_MAX_GROUPS], first[MOE_MAX_GROUPS + 1];
 };
 
+template <int ROWS = 256>
 __device__ __forceinline__ void tile_plan_build(TilePlan& pl, const FfnArgs& a, const GroupList& groups) {
   const int i = threadIdx.x;
   if (i < groups.n) {
@@ -382,7 +384,7 @@ __device__ __forceinline__ void tile_plan_build(TilePlan& pl, const FfnArgs& a, 
   __syncthreads();
   if (i <= groups.n) {
     int run = 0;
-    for (int q = 0; q < i; ++q) run += (pl.rows[q] + kTileRows - 1) / kTileRows;
+    for (int q = 0; q < i; ++q) run += (pl.rows[q] + ROWS - 1) / ROWS;
     pl.first[i] = run;
   }
   __syncthreads();
@@ -422,6 +424,7 @@ struct TileItem {
   int e, r0, row_end, slab;
 };
 
+template <int ROWS = 256>
 __device__ __forceinline__ TileItem tile_item(const GroupList& groups, const TilePlan& pl, int item,
                                               int slabs) {
   const int blk = item / slabs;
@@ -441,7 +444,7 @@ __device__ __forceinline__ TileItem tile_item(const GroupList& groups, const Til
   TileItem it;
   it.slab = item - blk * slabs;
   it.e = groups.id[g];
-  it.r0 = pl.begin[g] + (blk - pl.first[g]) * kTileRows;
+  it.r0 = pl.begin[g] + (blk - pl.first[g]) * ROWS;
   it.row_end = pl.begin[g] + pl.rows[g];
   return it;
 }
@@ -469,15 +472,16 @@ __device__ __forceinline__ void tile_rows(const FfnArgs& a, const TileItem& it, 
 }
 
 // Second half: the twelve source pointers of this lane (stage 0).
-template <int MODE>
+// (NQ = 12; the weights-in-registers form below asks for the token sources only, NQ = 8.)
+template <int MODE, int NQ>
 __device__ __forceinline__ void tile_sources(const FfnArgs& a, const ExpertTable& tab,
                                              const TileItem& it, const int (&ids)[8], int lane,
-                                             int wave, const uint16_t* (&src)[kFetchPerWave]) {
+                                             int wave, const uint16_t* (&src)[NQ]) {
   const int e = it.e;
   const int n0 = it.slab * (MODE == kGateUp ? 64 : 128);
   const int chunk = tile_fetch_chunk(lane);
 #pragma unroll
-  for (int q = 0; q < kFetchPerWave; ++q) {
+  for (int q = 0; q < NQ; ++q) {
     const int h = wave + 4 * q, blk = h >> 1, u = h & 1;
     const int rr = tile_fetch_row(lane, u);   // row inside the 16-row block
     if (q < 8) {
@@ -515,7 +519,7 @@ __device__ __forceinline__ void tile_sources(const FfnArgs& a, const ExpertTable
   // for table look-ups) sinks in between the fetches, and an in-order wait
   // there stalls on the fetches already issued
 #pragma unroll
-  for (int q = 0; q < kFetchPerWave; ++q) asm volatile("" : "+v"(src[q]));
+  for (int q = 0; q < NQ; ++q) asm volatile("" : "+v"(src[q]));
 }
 
 // Issue this wave's fetches of stage st into ring buffer st % 3: the first NTOK
@@ -666,7 +670,7 @@ __device__ __forceinline__ void ffn_tile_block(const FfnArgs& a, const ExpertTab
   if (has_next) {
     const uint16_t* next_src[kFetchPerWave];
     if (ns < 2) tile_rows<MODE>(a, nxt, lane, wave, next_ids);
-    tile_sources<MODE>(a, tab, nxt, next_ids, lane, wave, next_src);
+    tile_sources<MODE, kFetchPerWave>(a, tab, nxt, next_ids, lane, wave, next_src);
     asm volatile("s_barrier" ::: "memory");
     tile_fetch<8>(next_src, 0, w_adv, wave, ring);   // in full: the next item's size is not a constant here
     if (ns > 1) tile_fetch<8>(next_src, 1, w_adv, wave, ring);
@@ -706,7 +710,7 @@ __global__ __launch_bounds__(kThreads, 1) void ffn_tile_kernel(FfnArgs a, Expert
   {
     int rows[8];
     tile_rows<MODE>(a, it, lane, wave, rows);
-    tile_sources<MODE>(a, tab, it, rows, lane, wave, src);
+    tile_sources<MODE, kFetchPerWave>(a, tab, it, rows, lane, wave, src);
     tile_fetch<8>(src, 0, w_adv, wave, ring);
     if (a.K / kTileK > 1) tile_fetch<8>(src, 1, w_adv, wave, ring);
   }
@@ -726,21 +730,362 @@ __global__ __launch_bounds__(kThreads, 1) void ffn_tile_kernel(FfnArgs a, Expert
 }
 
 
-// Upper bound on the number of 256-row blocks a launch can need.
-int max_row_blocks(const moe_shape& s) {
-  return (s.T * s.k + s.S * s.T) / kTileRows + s.E + s.S + 1;
+// ------------------------------------- prefill: weights in registers ----
+// A second form of the tiled kernel for well-filled blocks (many rows per
+// expert).  Two measurements shape it.  A wavefront that is alone on its SIMD
+// issues a 16x16x32 MFMA only every ~27 clocks; two wavefronts sharing a SIMD
+// reach the pipe's 16.  And everything the form above multiplies goes through
+// the direct-to-LDS path, 48 KiB per stage for 256 x 128 x 64 multiply-adds.
+// Here a workgroup has EIGHT wavefronts, two per SIMD, and only the token rows
+// go through LDS.  The waves split the WEIGHT rows of a slab twice as wide
+// (gate/up: 16 gate + 16 up rows each, 128 columns of h per workgroup; down:
+// 32 rows each, 256 columns of y) and fetch their own weight tiles straight
+// into registers in MFMA operand layout, as the decode stream kernel does,
+// kWideWeightSets - 1 stages ahead.  Every wave multiplies all token tiles of
+// the 256-row block, read from a four-slot ring of 32 KiB stages: 64 KiB per
+// stage for 256 x 256 x 64 multiply-adds.  Same group list and block list, same
+// persistent loop with the next item's first token stages issued ahead of the
+// epilogue, same order of accumulation along the contraction.
+constexpr int kWideWaves = 8;
+constexpr int kWideThreads = kWideWaves * MOE_WAVE;
+constexpr int kWideTiles = 16;                     // token tiles of a block
+constexpr int kWideRows = 16 * kWideTiles;
+constexpr int kWideStage = kWideTiles * kDblFrag;  // 32 KiB
+constexpr int kWideStages = 4;                     // token ring
+constexpr int kWideWeightSets = 3;                 // weight stages in registers
+constexpr int kWideLds = kWideStage * kWideStages;
+constexpr int kWideFetch = 2 * kWideTiles / kWideWaves;   // token fetches per wave and stage
+constexpr int kWideSlabGateUp = 16 * kWideWaves;   // columns of h per item
+constexpr int kWideSlabDown = 32 * kWideWaves;     // columns of y per item
+constexpr int kWideWLead = kWideWeightSets - 1, kWideTLead = kWideStages - 1;
+constexpr int kWideTail = kWideWLead > kWideTLead ? kWideWLead : kWideTLead;   // stages that issue less
+constexpr int kWideMinStages = 2 + kWideWeightSets + kWideTail;   // shorter contractions use the form above
+static_assert(2 * kWideTiles % kWideWaves == 0, "token fetches must divide over the waves");
+
+// Loads a stage issues when d stages remain (itself included), and the number
+// of loads that are younger than the tokens of the stage with d remaining:
+// those of the two stages before it.
+constexpr int wide_issue_w(int d) { return d > kWideWLead ? 4 : 0; }
+constexpr int wide_issue_t(int d) { return d > kWideTLead ? kWideFetch : 0; }
+constexpr int wide_wait(int d) {
+  return wide_issue_w(d + 2) + wide_issue_t(d + 2) + wide_issue_w(d + 1) + wide_issue_t(d + 1);
+}
+
+// The token fetches of this form go through a buffer resource (base = the
+// activation matrix, one 32-bit byte offset per lane, the stage as a scalar
+// offset) rather than through per-lane 64-bit addresses: the compiler counts a
+// buffer instruction among the ordinary loads, so its own waits for the weight
+// registers come out exact.  (Behind a direct-to-LDS load in the flat-address
+// encoding it waits for every outstanding load instead.)
+using ActRsrc = __amdgpu_buffer_rsrc_t;
+
+__device__ __forceinline__ ActRsrc wide_resource(const FfnArgs& a, long long act_rows) {
+  // out-of-range reads return zero; the launcher keeps the matrix under 2 GiB
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.act), 0,
+                                           (int)(act_rows * a.K * 2), 0x00020000);
+}
+
+// Wave w issues the fetches h = w + 8 q of a stage: rows 8 (h & 1) .. of token
+// block h / 2.  First half of an item's set-up, as tile_rows above.
+template <int MODE>
+__device__ __forceinline__ void wide_rows(const FfnArgs& a, const TileItem& it, int lane, int wave,
+                                          int (&ids)[kWideFetch]) {
+#pragma unroll
+  for (int q = 0; q < kWideFetch; ++q) {
+    const int h = wave + kWideWaves * q, blk = h >> 1, u = h & 1;
+    const int p = min(it.r0 + blk * 16 + tile_fetch_row(lane, u), it.row_end - 1);
+    ids[q] = MODE == kGateUp ? a.perm[min(p, a.A - 1)] : 0;
+  }
+}
+
+// Second half: byte offsets of this lane's token fetches of stage 0.
+template <int MODE>
+__device__ __forceinline__ void wide_offsets(const FfnArgs& a, const TileItem& it,
+                                             const int (&ids)[kWideFetch], int lane, int wave,
+                                             uint32_t (&off)[kWideFetch]) {
+  const int e = it.e;
+  const int chunk = tile_fetch_chunk(lane);
+#pragma unroll
+  for (int q = 0; q < kWideFetch; ++q) {
+    const int h = wave + kWideWaves * q, blk = h >> 1, u = h & 1;
+    const int p = min(it.r0 + blk * 16 + tile_fetch_row(lane, u), it.row_end - 1);
+    int row = p;                                                 // down: h is in bucket order
+    if (MODE == kGateUp) row = e >= a.E ? p - (a.A + (e - a.E) * a.T) : ids[q] / a.k;
+    off[q] = ((uint32_t)row * a.K + chunk * 8) * 2;
+  }
+  // computed here, not between the fetches (see tile_sources)
+#pragma unroll
+  for (int q = 0; q < kWideFetch; ++q) asm volatile("" : "+v"(off[q]));
+}
+
+// Token fetches of stage st into ring slot st mod 4.
+__device__ __forceinline__ void wide_fetch(ActRsrc rsrc, const uint32_t (&off)[kWideFetch], int st,
+                                           int wave, unsigned char* ring) {
+  unsigned char* base = ring + (st % kWideStages) * kWideStage;
+#pragma unroll
+  for (int q = 0; q < kWideFetch; ++q)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+        rsrc,
+        (__attribute__((address_space(3))) void*)(base + (wave + kWideWaves * q) * kFragBytes), 16,
+        off[q], st * (kTileK * 2), 0, 0);
+}
+
+template <int V>
+using Tag = std::integral_constant<int, V>;
+
+// NT = token tiles multiplied (4, 8, 12 or 16): a compile-time bound.
+// R = (K/64 - 2 - kWideTail) % kWideWeightSets.
+template <int MODE, int NT, int R>
+__device__ __forceinline__ void ffn_wide_block(const FfnArgs& a, const ExpertTable& tab,
+                                               const TileItem& it, bool has_next,
+                                               const TileItem& nxt, ActRsrc rsrc,
+                                               uint32_t (&src)[kWideFetch],
+                                               unsigned char* ring) {
+  const int r0 = it.r0, row_end = it.row_end;
+  const int lane = threadIdx.x & (MOE_WAVE - 1), wave = threadIdx.x / MOE_WAVE;
+  const int n0 = it.slab * (MODE == kGateUp ? kWideSlabGateUp : kWideSlabDown);
+  // this wave's two weight tiles: gate/up -> 16 rows of Wg and the same rows of
+  // Wu; down -> 32 consecutive rows of Wd
+  const uint16_t* w[2];
+  int nrow[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const uint16_t* W;
+    if (MODE == kGateUp) {
+      W = static_cast<const uint16_t*>(i ? tab.Wu[it.e] : tab.Wg[it.e]);
+      nrow[i] = n0 + wave * 16;
+    } else {
+      W = static_cast<const uint16_t*>(tab.Wd[it.e]);
+      nrow[i] = n0 + wave * 32 + i * 16;
+    }
+    w[i] = W + weight_lane_offset(a.tiled, nrow[i] / 16, a.K, lane);
+  }
+  const int wstep = weight_kstep_stride(a.tiled);
+  int rd[2];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) rd[ks] = tile_read_offset(lane & 15, 4 * ks + (lane >> 4));
+
+  f32x4 acc[2][NT];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  int next_ids[kWideFetch];
+#pragma unroll
+  for (int q = 0; q < kWideFetch; ++q) next_ids[q] = 0;
+
+  const int ns = a.K / kTileK;
+  constexpr int WS = kWideWeightSets;
+  bf16x8 wreg[WS][2][2];                           // [stage % WS][k-step][tile]
+  auto load_w = [&](auto set_tag, int st) {
+    constexpr int SET = decltype(set_tag)::value;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        wreg[SET][ks][i] = *reinterpret_cast<const bf16x8*>(w[i] + (size_t)(2 * st + ks) * wstep);
+  };
+  load_w(Tag<0>{}, 0);
+  load_w(Tag<1>{}, 1);
+  if constexpr (WS > 3) load_w(Tag<2 % WS>{}, 2);
+  if constexpr (WS > 4) load_w(Tag<3 % WS>{}, 3);
+  static_assert(WS >= 3 && WS <= 5, "the preamble loads above cover three to five register sets");
+
+  // One stage.  Loads complete in order; a stage issues weights(st + WS - 1) and
+  // tokens(st + 3).  tokens(st) were issued in stage st - 3 (or before the item
+  // began, ahead of its first weight loads), and whatever the two stages since
+  // then issued is younger: "at most that many outstanding" says tokens(st)
+  // have landed.  The compiler adds its own exact waits for the weight
+  // registers.  The last stages issue less (D = stages remaining decides), so
+  // they wait for fewer.  All of this is fixed at compile time: a stage has no
+  // branches, which keeps the compiler's load bookkeeping exact.
+  auto stage = [&](int st, auto set_tag, auto remaining_tag, auto rows_tag) {
+    constexpr int SET = decltype(set_tag)::value;
+    constexpr int D = decltype(remaining_tag)::value;
+    constexpr bool IW = wide_issue_w(D) > 0, IT = wide_issue_t(D) > 0;
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(wide_wait(D)) : "memory");
+    if (decltype(rows_tag)::value && has_next) wide_rows<MODE>(a, nxt, lane, wave, next_ids);
+    if (IW) load_w(Tag<(SET + kWideWLead) % WS>{}, st + kWideWLead);
+    if (IT) wide_fetch(rsrc, src, st + kWideTLead, wave, ring);
+    const unsigned char* base = ring + (st % kWideStages) * kWideStage;
+    bf16x8 tf[2][NT];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+        tf[ks][j] = *reinterpret_cast<const bf16x8*>(base + j * kDblFrag + rd[ks]);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[SET][ks][i], tf[ks][j], acc[i][j], 0, 0, 0);
+    // order for the scheduler: the loads, some LDS reads ahead, then one more
+    // read per two MFMAs
+    constexpr int AHEAD = 6;
+    if (IW || IT) __builtin_amdgcn_sched_group_barrier(0x020, (IW ? 4 : 0) + (IT ? kWideFetch : 0), 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, AHEAD, 0);
+#pragma unroll
+    for (int q = 0; q < 2 * NT - AHEAD; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 2 * AHEAD, 0);
+  };
+  // ns = 2 + R + WS m + kWideTail stages (the launcher picks R): 0 and 1, R more
+  // at full issue, m rounds of WS, then the kWideTail that issue less and less
+  constexpr int FULL = kWideTail + 1;              // any "stages remaining" above the tail
+  constexpr int S0 = (2 + R) % WS;                 // register set of the first looped stage
+  stage(0, Tag<0>{}, Tag<FULL>{}, Tag<0>{});
+  stage(1, Tag<1>{}, Tag<FULL>{}, Tag<1>{});
+  if constexpr (R >= 1) stage(2, Tag<2 % WS>{}, Tag<FULL>{}, Tag<0>{});
+  if constexpr (R >= 2) stage(3, Tag<3 % WS>{}, Tag<FULL>{}, Tag<0>{});
+  if constexpr (R >= 3) stage(4, Tag<4 % WS>{}, Tag<FULL>{}, Tag<0>{});
+  if constexpr (R >= 4) stage(5, Tag<5 % WS>{}, Tag<FULL>{}, Tag<0>{});
+  int st = 2 + R;
+  for (; st < ns - kWideTail; st += WS) {
+    stage(st, Tag<S0>{}, Tag<FULL>{}, Tag<0>{});
+    stage(st + 1, Tag<(S0 + 1) % WS>{}, Tag<FULL>{}, Tag<0>{});
+    stage(st + 2, Tag<(S0 + 2) % WS>{}, Tag<FULL>{}, Tag<0>{});
+    if constexpr (WS > 3) stage(st + 3, Tag<(S0 + 3) % WS>{}, Tag<FULL>{}, Tag<0>{});
+    if constexpr (WS > 4) stage(st + 4, Tag<(S0 + 4) % WS>{}, Tag<FULL>{}, Tag<0>{});
+  }
+  if constexpr (kWideTail >= 4) stage(ns - 4, Tag<(S0 + kWideTail + WS - 4) % WS>{}, Tag<4>{}, Tag<0>{});
+  stage(ns - 3, Tag<(S0 + kWideTail - 3) % WS>{}, Tag<3>{}, Tag<0>{});
+  stage(ns - 2, Tag<(S0 + kWideTail - 2) % WS>{}, Tag<2>{}, Tag<0>{});
+  stage(ns - 1, Tag<(S0 + kWideTail - 1) % WS>{}, Tag<1>{}, Tag<0>{});
+  static_assert(kWideTail == 3 || kWideTail == 4, "tail stages are written out for three or four");
+
+  // D layout: lane holds rows 4*g .. 4*g+3 of the 16-row weight tile, column r = token
+  auto epilogue = [&]() {
+    const int r = lane & 15, g = lane >> 4;
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      const int p = r0 + j * 16 + r;
+      if (p >= row_end) continue;
+      if (MODE == kGateUp) {
+        uint16_t* h = static_cast<uint16_t*>(a.out);
+        float hv[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) hv[q] = silu_f(acc[0][j][q]) * acc[1][j][q];
+        uint2 pk;
+        pk.x = pack_bf16x2(hv[0], hv[1]);
+        pk.y = pack_bf16x2(hv[2], hv[3]);
+        *reinterpret_cast<uint2*>(h + (size_t)p * a.N + nrow[0] + 4 * g) = pk;
+      } else {
+        float* y = static_cast<float*>(a.out);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+          *reinterpret_cast<float4*>(y + (size_t)p * a.N + nrow[i] + 4 * g) =
+              make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+      }
+    }
+  };
+
+  // The ring is free once every wave has read the last stage: start the next
+  // item, then write this one's results while those fetches fly.
+  if (has_next) {
+    uint32_t next_src[kWideFetch];
+    wide_offsets<MODE>(a, nxt, next_ids, lane, wave, next_src);
+    asm volatile("s_barrier" ::: "memory");
+#pragma unroll
+    for (int q = 0; q < kWideTLead; ++q) wide_fetch(rsrc, next_src, q, wave, ring);
+    epilogue();
+#pragma unroll
+    for (int q = 0; q < kWideFetch; ++q) src[q] = next_src[q];
+  } else {
+    epilogue();
+  }
+}
+
+template <int MODE, int R>
+__global__ __launch_bounds__(kWideThreads, 1) void ffn_wide_kernel(FfnArgs a, ExpertTable tab,
+                                                                   GroupList groups,
+                                                                   long long act_rows) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char ring[];
+  __shared__ TilePlan plan;
+  tile_plan_build<kWideRows>(plan, a, groups);
+  const int slabs = a.N / (MODE == kGateUp ? kWideSlabGateUp : kWideSlabDown);
+  const int total = plan.first[groups.n] * slabs;
+  const int per_xcd = (total + 7) / 8;
+  const int xcd = blockIdx.x & 7, stride = gridDim.x >> 3;   // grid is a multiple of 8
+  int local = blockIdx.x >> 3;
+  const int lo = xcd * per_xcd, hi = min(lo + per_xcd, total);
+  if (lo + local >= hi) return;
+  const int lane = threadIdx.x & (MOE_WAVE - 1), wave = threadIdx.x / MOE_WAVE;
+
+  TileItem it = tile_item<kWideRows>(groups, plan, lo + local, slabs);
+  const ActRsrc rsrc = wide_resource(a, act_rows);
+  uint32_t src[kWideFetch];
+  {
+    int ids[kWideFetch];
+    wide_rows<MODE>(a, it, lane, wave, ids);
+    wide_offsets<MODE>(a, it, ids, lane, wave, src);
+#pragma unroll
+    for (int q = 0; q < kWideTLead; ++q) wide_fetch(rsrc, src, q, wave, ring);
+  }
+  while (true) {
+    const bool has_next = lo + local + stride < hi;
+    TileItem nxt = it;
+    if (has_next) nxt = tile_item<kWideRows>(groups, plan, lo + local + stride, slabs);
+    const int tiles = (min(it.row_end - it.r0, kWideRows) + 15) / 16;
+    if (tiles <= 4) ffn_wide_block<MODE, 4, R>(a, tab, it, has_next, nxt, rsrc, src, ring);
+    else if (tiles <= 8) ffn_wide_block<MODE, 8, R>(a, tab, it, has_next, nxt, rsrc, src, ring);
+    else if (tiles <= 12) ffn_wide_block<MODE, 12, R>(a, tab, it, has_next, nxt, rsrc, src, ring);
+    else ffn_wide_block<MODE, 16, R>(a, tab, it, has_next, nxt, rsrc, src, ring);
+    if (!has_next) break;
+    it = nxt;
+    local += stride;
+  }
+}
+
+template <int MODE, int R = 0>
+struct WideKernels {
+  static const void* get(int r) {
+    if (r == R) return reinterpret_cast<const void*>(&ffn_wide_kernel<MODE, R>);
+    if constexpr (R + 1 < kWideWeightSets) return WideKernels<MODE, R + 1>::get(r);
+    return nullptr;
+  }
+};
+
+// Upper bound on the number of row blocks a launch can need.
+int max_row_blocks(const moe_shape& s, int block_rows) {
+  return (s.T * s.k + s.S * s.T) / block_rows + s.E + s.S + 1;
+}
+
+// Within the tiled family: the weights-in-registers form once the blocks are
+// well filled, if the output width is a multiple of its slab, the contraction
+// is long enough for its fixed pipeline and the activation matrix fits a
+// 32-bit buffer offset.  MOE_TUNE_WIDE=0|1 overrides the first
+// condition (measurement aid).
+bool wide_form(const moe_shape& s, int phase) {
+  const long long K = phase == 0 ? s.H : s.F;
+  const long long act_rows = phase == 0 ? (long long)s.T : (long long)s.T * s.k + (long long)s.S * s.T;
+  const int N = phase == 0 ? s.F : s.H;
+  if (N % (phase == 0 ? kWideSlabGateUp : kWideSlabDown) != 0) return false;
+  if (K / kTileK < kWideMinStages || act_rows * K * 2 >= (1ll << 31)) return false;
+  static const char* env = getenv("MOE_TUNE_WIDE");
+  if (env && (env[0] == '0' || env[0] == '1')) return env[0] == '1';
+  const double rows = (double)s.T * s.k / s.E;
+  return rows >= 96.0 || (s.S > 0 && s.T > 256);
 }
 
 template <int MODE>
 moe_status launch_tile(const moe_shape& s, const FfnArgs& args, const ExpertTable& tab,
-                       const GroupList& groups, hipStream_t stream) {
+                       const GroupList& groups, hipStream_t stream, bool wide) {
   static bool attr_set = false;
   if (!attr_set) {
     MOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_tile_kernel<MODE>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kTileLds));
+    for (int r = 0; r < kWideWeightSets; ++r)
+      MOE_HIP(hipFuncSetAttribute(WideKernels<MODE>::get(r),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, kWideLds));
     attr_set = true;
   }
-  const int slabs = MODE == kGateUp ? s.F / 64 : s.H / 128;
+  const int slabs = wide ? (MODE == kGateUp ? s.F / kWideSlabGateUp : s.H / kWideSlabDown)
+                         : (MODE == kGateUp ? s.F / 64 : s.H / 128);
   // one persistent workgroup per compute unit, never more than there can be items
   static int n_cu = 0;
   if (!n_cu) {
@@ -748,9 +1093,19 @@ moe_status launch_tile(const moe_shape& s, const FfnArgs& args, const ExpertTabl
     MOE_HIP(hipGetDevice(&dev));
     MOE_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
   }
-  const int grid = (std::min(slabs * max_row_blocks(s), n_cu) + 7) / 8 * 8;
-  hipLaunchKernelGGL((ffn_tile_kernel<MODE>), dim3(grid), dim3(kThreads), kTileLds, stream, args,
-                     tab, groups);
+  const int grid = (std::min(slabs * max_row_blocks(s, wide ? kWideRows : kTileRows), n_cu) + 7) / 8 * 8;
+  if (wide) {
+    // rows of the activation matrix: tokens for gate/up, bucket rows for down
+    long long act_rows = MODE == kGateUp ? (long long)s.T : (long long)args.A + (long long)s.S * s.T;
+    FfnArgs wargs = args;
+    void* params[] = {&wargs, const_cast<ExpertTable*>(&tab), const_cast<GroupList*>(&groups), &act_rows};
+    const int r = (args.K / kTileK - 2 - kWideTail) % kWideWeightSets;
+    MOE_HIP(hipLaunchKernel(WideKernels<MODE>::get(r), dim3(grid), dim3(kWideThreads), params,
+                            kWideLds, stream));
+  } else {
+    hipLaunchKernelGGL((ffn_tile_kernel<MODE>), dim3(grid), dim3(kThreads), kTileLds, stream, args,
+                       tab, groups);
+  }
   MOE_HIP(hipGetLastError());
   return MOE_OK;
 }
@@ -1022,7 +1377,7 @@ moe_status launch_ffn_gate_up(const moe_shape& s, const void* X, const int32_t* 
                s.weight_layout == MOE_TILED};
     const Variant v = gate_up_variant(s, groups.n);
     if (v == kTile && tile_kernel_fits(s)) {
-      return launch_tile<kGateUp>(s, gu, tab, groups, stream);
+      return launch_tile<kGateUp>(s, gu, tab, groups, stream, wide_form(s, 0));
     } else if (v != kStream64) {
       hipLaunchKernelGGL((ffn_stream_kernel<kGateUp, 8, 1>), dim3(s.F / (kWaves * 16), groups.n, (s.T + 127) / 128),
                          dim3(kThreads), 0, stream, gu, tab, groups);
@@ -1053,7 +1408,7 @@ moe_status launch_ffn_down(const moe_shape& s, const FfnScratch& scratch, const 
                s.weight_layout == MOE_TILED};
     const Variant v = down_variant(s);
     if (v == kTile && tile_kernel_fits(s)) {
-      return launch_tile<kDown>(s, dn, tab, groups, stream);
+      return launch_tile<kDown>(s, dn, tab, groups, stream, wide_form(s, 1));
     } else if (v == kHalves) {
       hipLaunchKernelGGL((ffn_stream_kernel<kDownHalves, 4, 1>), dim3(s.H / (kWaves * 16), groups.n, (s.T + 63) / 64),
                          dim3(kThreads), 0, stream, dn, tab, groups);
@@ -1106,7 +1461,9 @@ const char* ffn_kernel_name(const moe_shape& s, int phase, int n_groups) {
   if (s.dtype != MOE_BF16) return phase == 0 ? "ffn_f32_kernel<gate/up>" : "ffn_f32_kernel<down>";
   const Variant v = phase == 0 ? gate_up_variant(s, n_groups) : down_variant(s);
   switch (v) {
-    case kTile: return phase == 0 ? "ffn_tile_kernel<gate/up>" : "ffn_tile_kernel<down>";
+    case kTile:
+      if (wide_form(s, phase)) return phase == 0 ? "ffn_wide_kernel<gate/up>" : "ffn_wide_kernel<down>";
+      return phase == 0 ? "ffn_tile_kernel<gate/up>" : "ffn_tile_kernel<down>";
     case kSplitK: return "ffn_down_splitk_kernel";
     case kHalves: return "ffn_stream_kernel<down, halved contraction>";
     case kStream64: return phase == 0 ? "ffn_stream_kernel<gate/up, 64 rows>" : "ffn_stream_kernel<down, 64 rows>";

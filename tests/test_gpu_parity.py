@@ -78,6 +78,10 @@ SMALL = [
     _small("s_bf16_128row_passes", T=200, E=60, k=4, S=1, H=128, F=256, bias="zipf", bias_scale=1.1),
     _small("s_bf16_wide_decode", T=12, E=8, k=2, H=128, F=4096),
     _small("s_bf16_wide_halves", T=40, E=8, k=2, H=128, F=4096),
+    # well-filled blocks: the eight-wave tiled form, all three pipeline remainders
+    # (contraction lengths of 8, 10 and 12 stages), uneven and split blocks
+    _small("s_bf16_filled_blocks", T=400, E=4, k=2, H=512, F=640, S=1, bias="zipf", bias_scale=0.7),
+    _small("s_bf16_filled_blocks_12", T=300, E=2, k=1, H=768, F=768, S=1),
 ]
 
 
@@ -427,7 +431,8 @@ def test_small_configs_reach_every_ffn_kernel(B):
         sh = _shape(B, cfg, layout="tiled")
         for phase in (0, 1):
             seen.add(B.moe_ffn_kernel_name(sh, phase, cfg.E + cfg.S))
-    want = {"ffn_tile_kernel<gate/up>", "ffn_tile_kernel<down>", "ffn_down_splitk_kernel",
+    want = {"ffn_tile_kernel<gate/up>", "ffn_tile_kernel<down>", "ffn_wide_kernel<gate/up>",
+            "ffn_wide_kernel<down>", "ffn_down_splitk_kernel",
             "ffn_stream_kernel<down, halved contraction>", "ffn_stream_kernel<gate/up, 64 rows>",
             "ffn_stream_kernel<down, 64 rows>", "ffn_stream_kernel<gate/up, 128 rows>",
             "ffn_stream_kernel<down, 128 rows>", "ffn_f32_kernel<gate/up>", "ffn_f32_kernel<down>"}
