@@ -106,7 +106,8 @@ def hbm_probe(torch, B):
     big.view(torch.int32).random_(0, 1 << 30)
     sink = torch.zeros(4, dtype=torch.uint8, device="cuda")
     for name, fn, nbytes in (("copy_1GiB", lambda: B.moe_probe_copy(dst, src), 2 * (1 << 30)),
-                             ("read_4GiB", lambda: B.moe_probe_read(big, sink), 4 << 30)):
+                             ("read_4GiB", lambda: B.moe_probe_read(big, sink), 4 << 30),
+                             ("read_nt_4GiB", lambda: B.moe_probe_read_nt(big, sink), 4 << 30)):
         for _ in range(3):
             fn()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

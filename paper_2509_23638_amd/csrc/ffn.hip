@@ -88,7 +88,7 @@ __device__ __forceinline__ float silu_f(float z) {
 // owns 64 rows instead of 128, so a Mixtral-shaped down projection has twice
 // the workgroups (two per compute unit, like gate/up) and twice the weight
 // bytes in flight.  The halves need different activations: LDS holds both.
-template <int MODE, int NT, int TB, int RT>
+template <int MODE, int NT, int TB, int RT, bool ONCE>
 struct Streamer {
   static constexpr bool kHalves = MODE == kDownHalves;
   static constexpr int NH = kHalves ? 2 : 1;          // activation positions staged per chunk
@@ -114,8 +114,18 @@ struct Streamer {
     for (int s = 0; s < kStepsPerChunk; ++s)
 #pragma unroll
       for (int i = 0; i < NA; ++i)
-        wreg[SET][s][i] = *reinterpret_cast<const bf16x8*>(
-            w[i] + (size_t)(c * kStepsPerChunk + s) * wstep);
+        wreg[SET][s][i] = load_weight(w[i] + (size_t)(c * kStepsPerChunk + s) * wstep);
+  }
+
+  // ONCE: no other workgroup reads this weight tile (the expert's bucket fits
+  // one pass), so it is loaded non-temporal: it is not kept in L2, where it
+  // would only push out lines that are read again.  Measured on a
+  // Mixtral-shaped layer the weight stream gains 8-10 % from this; with several
+  // passes per expert it loses as much.  (A compile-time choice: given both
+  // kinds of load behind a run-time flag the compiler emits the plain one.)
+  __device__ __forceinline__ bf16x8 load_weight(const uint16_t* p) const {
+    const bf16x8* q = reinterpret_cast<const bf16x8*>(p);
+    return ONCE ? __builtin_nontemporal_load(q) : *q;
   }
 
   // wave w fetches k-step w of every tile of chunk c
@@ -212,12 +222,12 @@ struct Streamer {
 
 // One workgroup: expert `e`, output rows [n0, n0 + rows per WG), bucket rows
 // [r0, min(r0 + 16*TB, row_end)).
-template <int MODE, int NT, int TB, int RT>
+template <int MODE, int NT, int TB, int RT, bool ONCE>
 __device__ __forceinline__ void ffn_block(const FfnArgs& a, const uint16_t* W0, const uint16_t* W1,
                                           int n0, int r0, int row_end, int shared_base,
                                           unsigned char* lds) {
   constexpr int NA = 2 * RT;
-  Streamer<MODE, NT, TB, RT> st(a);
+  Streamer<MODE, NT, TB, RT, ONCE> st(a);
   st.lds = lds;
   st.lane = threadIdx.x & (MOE_WAVE - 1);
   st.wave = threadIdx.x / MOE_WAVE;
@@ -281,6 +291,27 @@ __device__ __forceinline__ void ffn_block(const FfnArgs& a, const uint16_t* W0, 
   }
 }
 
+// rows past the bucket's end are clamped on load and dropped on store, so a
+// larger tile count than needed is only wasted arithmetic
+template <int MODE, int TB, int RT, bool ONCE>
+__device__ __forceinline__ void ffn_block_sized(int nt, const FfnArgs& a, const uint16_t* W0,
+                                                const uint16_t* W1, int n0, int r0, int row_end,
+                                                int shared_base, unsigned char* lds) {
+  if (TB <= 4) {
+    switch (nt) {
+      case 1: ffn_block<MODE, 1, TB, RT, ONCE>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
+      case 2: ffn_block<MODE, 2, TB, RT, ONCE>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
+      case 3: ffn_block<MODE, 3, TB, RT, ONCE>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
+      default: ffn_block<MODE, 4, TB, RT, ONCE>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
+    }
+  } else {
+    if (nt <= 2) ffn_block<MODE, 2, TB, RT, ONCE>(a, W0, W1, n0, r0, row_end, shared_base, lds);
+    else if (nt <= 4) ffn_block<MODE, 4, TB, RT, ONCE>(a, W0, W1, n0, r0, row_end, shared_base, lds);
+    else if (nt <= 6) ffn_block<MODE, 6, TB, RT, ONCE>(a, W0, W1, n0, r0, row_end, shared_base, lds);
+    else ffn_block<MODE, TB, TB, RT, ONCE>(a, W0, W1, n0, r0, row_end, shared_base, lds);
+  }
+}
+
 template <int MODE, int TB, int RT>
 __global__ __launch_bounds__(kThreads) void ffn_stream_kernel(FfnArgs a, ExpertTable tab,
                                                               GroupList groups) {
@@ -312,21 +343,11 @@ __global__ __launch_bounds__(kThreads) void ffn_stream_kernel(FfnArgs a, ExpertT
     W0 = W1 = static_cast<const uint16_t*>(tab.Wd[e]);
     n0 = blockIdx.x * (kWaves * 32 * RT);
   }
-  // rows past the bucket's end are clamped on load and dropped on store, so a
-  // larger tile count than needed is only wasted arithmetic
-  if (TB <= 4) {
-    switch (nt) {
-      case 1: ffn_block<MODE, 1, TB, RT>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
-      case 2: ffn_block<MODE, 2, TB, RT>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
-      case 3: ffn_block<MODE, 3, TB, RT>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
-      default: ffn_block<MODE, 4, TB, RT>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
-    }
-  } else {
-    if (nt <= 2) ffn_block<MODE, 2, TB, RT>(a, W0, W1, n0, r0, row_end, shared_base, lds);
-    else if (nt <= 4) ffn_block<MODE, 4, TB, RT>(a, W0, W1, n0, r0, row_end, shared_base, lds);
-    else if (nt <= 6) ffn_block<MODE, 6, TB, RT>(a, W0, W1, n0, r0, row_end, shared_base, lds);
-    else ffn_block<MODE, TB, TB, RT>(a, W0, W1, n0, r0, row_end, shared_base, lds);
-  }
+  // whole bucket in this one pass: nobody else reads these weight rows
+  if (blockIdx.z == 0 && row_end - r0 <= kTokBlock)
+    ffn_block_sized<MODE, TB, RT, true>(nt, a, W0, W1, n0, r0, row_end, shared_base, lds);
+  else
+    ffn_block_sized<MODE, TB, RT, false>(nt, a, W0, W1, n0, r0, row_end, shared_base, lds);
 }
 
 // ------------------------------------------------ prefill: tiled kernel ----
@@ -533,9 +554,16 @@ __device__ __forceinline__ void tile_fetch(const uint16_t* const (&src)[kFetchPe
 #pragma unroll
   for (int q = 0; q < kFetchPerWave; ++q) {
     if (q >= NTOK && q < 8) continue;
-    __builtin_amdgcn_global_load_lds(
-        (const __attribute__((address_space(1))) void*)(src[q] + (size_t)st * (q >= 8 ? w_adv : kTileK)),
-        (__attribute__((address_space(3))) void*)(base + (wave + 4 * q) * kFragBytes), 16, 0, 0);
+    // weights are read once: marked non-temporal, so that they do not push the
+    // token rows (re-read by every slab of a block) out of L2
+    if (q >= 8)
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(src[q] + (size_t)st * w_adv),
+          (__attribute__((address_space(3))) void*)(base + (wave + 4 * q) * kFragBytes), 16, 0, 2);
+    else
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(src[q] + (size_t)st * kTileK),
+          (__attribute__((address_space(3))) void*)(base + (wave + 4 * q) * kFragBytes), 16, 0, 0);
   }
 }
 
@@ -883,8 +911,12 @@ __device__ __forceinline__ void ffn_wide_block(const FfnArgs& a, const ExpertTab
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-        wreg[SET][ks][i] = *reinterpret_cast<const bf16x8*>(w[i] + (size_t)(2 * st + ks) * wstep);
+      for (int i = 0; i < 2; ++i) {
+        // gate/up weights non-temporal (see Streamer::load_weight); for the down
+        // projection it measured slower in this kernel
+        const bf16x8* q = reinterpret_cast<const bf16x8*>(w[i] + (size_t)(2 * st + ks) * wstep);
+        wreg[SET][ks][i] = MODE == kGateUp ? __builtin_nontemporal_load(q) : *q;
+      }
   };
   load_w(Tag<0>{}, 0);
   load_w(Tag<1>{}, 1);
@@ -1118,7 +1150,7 @@ moe_status launch_tile(const moe_shape& s, const FfnArgs& args, const ExpertTabl
 // another wave's activations, so the B fragments go from global memory (h is a
 // few MB and lives in L2) straight to registers: no LDS and no barrier in the
 // loop.  The four partial accumulators meet in LDS once, summed in wave order.
-template <int NT>
+template <int NT, bool ONCE>
 struct SplitKStreamer {
   const uint16_t* w0;
   const uint16_t* w1;
@@ -1127,6 +1159,11 @@ struct SplitKStreamer {
   bf16x8 wreg[2][kStepsPerChunk][2];
   bf16x8 breg[2][NT][kStepsPerChunk];
   f32x4 acc0[NT], acc1[NT];
+
+  __device__ __forceinline__ bf16x8 load_weight(const uint16_t* p) const {
+    const bf16x8* q = reinterpret_cast<const bf16x8*>(p);
+    return ONCE ? __builtin_nontemporal_load(q) : *q;   // see Streamer::load_weight
+  }
 
   template <int SET>
   __device__ __forceinline__ void load(int c) {
@@ -1137,8 +1174,8 @@ struct SplitKStreamer {
         breg[SET][t][s] = *reinterpret_cast<const bf16x8*>(b[t] + (size_t)c * kChunk + s * kKStep);
 #pragma unroll
     for (int s = 0; s < kStepsPerChunk; ++s) {
-      wreg[SET][s][0] = *reinterpret_cast<const bf16x8*>(w0 + (size_t)(c * kStepsPerChunk + s) * wstep);
-      wreg[SET][s][1] = *reinterpret_cast<const bf16x8*>(w1 + (size_t)(c * kStepsPerChunk + s) * wstep);
+      wreg[SET][s][0] = load_weight(w0 + (size_t)(c * kStepsPerChunk + s) * wstep);
+      wreg[SET][s][1] = load_weight(w1 + (size_t)(c * kStepsPerChunk + s) * wstep);
     }
   }
 
@@ -1175,12 +1212,12 @@ struct SplitKStreamer {
 constexpr int kSplitRows = 32;   // weight rows per workgroup
 constexpr int kSplitTok = 32;    // bucket rows per pass (NT <= 2)
 
-template <int NT>
+template <int NT, bool ONCE>
 __device__ __forceinline__ void down_splitk_block(const FfnArgs& a, const uint16_t* Wd, int n0,
                                                   int r0, int row_end, float* red) {
   const int lane = threadIdx.x & (MOE_WAVE - 1), wave = threadIdx.x / MOE_WAVE;
   const int r = lane & 15, g = lane >> 4;
-  SplitKStreamer<NT> st;
+  SplitKStreamer<NT, ONCE> st;
   st.wstep = weight_kstep_stride(a.tiled);
   st.w0 = Wd + weight_lane_offset(a.tiled, n0 / 16, a.K, lane);
   st.w1 = Wd + weight_lane_offset(a.tiled, n0 / 16 + 1, a.K, lane);
@@ -1232,8 +1269,14 @@ __global__ __launch_bounds__(kThreads) void ffn_down_splitk_kernel(FfnArgs a, Ex
   if (r0 >= row_end) return;
   const uint16_t* Wd = static_cast<const uint16_t*>(tab.Wd[e]);
   const int n0 = blockIdx.x * kSplitRows;
-  if (row_end - r0 <= 16) down_splitk_block<1>(a, Wd, n0, r0, row_end, red);
-  else down_splitk_block<2>(a, Wd, n0, r0, row_end, red);
+  const bool once = blockIdx.z == 0 && row_end - r0 <= kSplitTok;   // the bucket's only pass
+  if (row_end - r0 <= 16) {
+    if (once) down_splitk_block<1, true>(a, Wd, n0, r0, row_end, red);
+    else down_splitk_block<1, false>(a, Wd, n0, r0, row_end, red);
+  } else {
+    if (once) down_splitk_block<2, true>(a, Wd, n0, r0, row_end, red);
+    else down_splitk_block<2, false>(a, Wd, n0, r0, row_end, red);
+  }
 }
 
 // ---------------------------------------------------------------- float32 --
