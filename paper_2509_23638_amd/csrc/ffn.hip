@@ -443,6 +443,7 @@ __device__ __forceinline__ int tile_read_offset(int r, int c) {
 // times one slab of its weight rows.
 struct TileItem {
   int e, r0, row_end, slab;
+  bool single;   // the expert's bucket is this one block
 };
 
 template <int ROWS = 256>
@@ -467,6 +468,7 @@ __device__ __forceinline__ TileItem tile_item(const GroupList& groups, const Til
   it.e = groups.id[g];
   it.r0 = pl.begin[g] + (blk - pl.first[g]) * ROWS;
   it.row_end = pl.begin[g] + pl.rows[g];
+  it.single = pl.rows[g] <= ROWS;
   return it;
 }
 
@@ -862,8 +864,8 @@ template <int V>
 using Tag = std::integral_constant<int, V>;
 
 // NT = token tiles multiplied (4, 8, 12 or 16): a compile-time bound.
-// R = (K/64 - 2 - kWideTail) % kWideWeightSets.
-template <int MODE, int NT, int R>
+// R = (K/64 - 2 - kWideTail) % kWideWeightSets.  ONCE: no other block reads these weight tiles.
+template <int MODE, int NT, int R, bool ONCE>
 __device__ __forceinline__ void ffn_wide_block(const FfnArgs& a, const ExpertTable& tab,
                                                const TileItem& it, bool has_next,
                                                const TileItem& nxt, ActRsrc rsrc,
@@ -912,10 +914,9 @@ __device__ __forceinline__ void ffn_wide_block(const FfnArgs& a, const ExpertTab
     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        // gate/up weights non-temporal (see Streamer::load_weight); for the down
-        // projection it measured slower in this kernel
+        // non-temporal when nobody reads the tile again (see Streamer::load_weight)
         const bf16x8* q = reinterpret_cast<const bf16x8*>(w[i] + (size_t)(2 * st + ks) * wstep);
-        wreg[SET][ks][i] = MODE == kGateUp ? __builtin_nontemporal_load(q) : *q;
+        wreg[SET][ks][i] = ONCE ? __builtin_nontemporal_load(q) : *q;
       }
   };
   load_w(Tag<0>{}, 0);
@@ -1063,10 +1064,24 @@ __global__ __launch_bounds__(kWideThreads, 1) void ffn_wide_kernel(FfnArgs a, Ex
     TileItem nxt = it;
     if (has_next) nxt = tile_item<kWideRows>(groups, plan, lo + local + stride, slabs);
     const int tiles = (min(it.row_end - it.r0, kWideRows) + 15) / 16;
-    if (tiles <= 4) ffn_wide_block<MODE, 4, R>(a, tab, it, has_next, nxt, rsrc, src, ring);
-    else if (tiles <= 8) ffn_wide_block<MODE, 8, R>(a, tab, it, has_next, nxt, rsrc, src, ring);
-    else if (tiles <= 12) ffn_wide_block<MODE, 12, R>(a, tab, it, has_next, nxt, rsrc, src, ring);
-    else ffn_wide_block<MODE, 16, R>(a, tab, it, has_next, nxt, rsrc, src, ring);
+    // gate/up weights of an expert with a single block: non-temporal.  (For the
+    // down projection the hint measured slower in this kernel.)
+    bool done = false;
+    if constexpr (MODE == kGateUp) {
+      if (it.single) {
+        if (tiles <= 4) ffn_wide_block<MODE, 4, R, true>(a, tab, it, has_next, nxt, rsrc, src, ring);
+        else if (tiles <= 8) ffn_wide_block<MODE, 8, R, true>(a, tab, it, has_next, nxt, rsrc, src, ring);
+        else if (tiles <= 12) ffn_wide_block<MODE, 12, R, true>(a, tab, it, has_next, nxt, rsrc, src, ring);
+        else ffn_wide_block<MODE, 16, R, true>(a, tab, it, has_next, nxt, rsrc, src, ring);
+        done = true;
+      }
+    }
+    if (!done) {
+      if (tiles <= 4) ffn_wide_block<MODE, 4, R, false>(a, tab, it, has_next, nxt, rsrc, src, ring);
+      else if (tiles <= 8) ffn_wide_block<MODE, 8, R, false>(a, tab, it, has_next, nxt, rsrc, src, ring);
+      else if (tiles <= 12) ffn_wide_block<MODE, 12, R, false>(a, tab, it, has_next, nxt, rsrc, src, ring);
+      else ffn_wide_block<MODE, 16, R, false>(a, tab, it, has_next, nxt, rsrc, src, ring);
+    }
     if (!has_next) break;
     it = nxt;
     local += stride;
