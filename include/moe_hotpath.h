@@ -304,8 +304,9 @@ moe_status moe_phase_times_get(moe_ctx* ctx, moe_phase_times* out, int32_t reset
  * for scaling hardware byte counters. */
 moe_status moe_probe_copy(void* dst, const void* src, size_t bytes, void* stream);
 moe_status moe_probe_read(const void* src, size_t bytes, void* sink4, void* stream);
-/* The same read with non-temporal loads (the hint the FFN kernels put on weight
- * tiles that are read once). */
+/* The same bytes read with non-temporal loads (the hint the FFN kernels put on
+ * weight tiles that are read once), eight 1 KiB loads in flight per wavefront
+ * over 8 KiB in a row. */
 moe_status moe_probe_read_nt(const void* src, size_t bytes, void* sink4, void* stream);
 
 /* Which kernel the grouped FFN launches for a shape (measurement aid for
