@@ -907,7 +907,8 @@ __device__ __forceinline__ void ffn_wide_block(const FfnArgs& a, const ExpertTab
                                                uint32_t (&src)[kWideFetch],
                                                unsigned char* ring) {
   const int r0 = it.r0, row_end = it.row_end;
-  const int lane = threadIdx.x & (MOE_WAVE - 1), wave = threadIdx.x / MOE_WAVE;
+  const int lane = threadIdx.x & (MOE_WAVE - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE);   // uniform: a scalar register
   const int n0 = it.slab * (MODE == kGateUp ? kWideSlabGateUp : kWideSlabDown);
   // this wave's two weight tiles: gate/up -> 16 rows of Wg and the same rows of
   // Wu; down -> 32 consecutive rows of Wd
@@ -973,7 +974,14 @@ __device__ __forceinline__ void ffn_wide_block(const FfnArgs& a, const ExpertTab
     constexpr int D = decltype(remaining_tag)::value;
     constexpr bool IW = wide_issue_w(D) > 0, IT = wide_issue_t(D) > 0;
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(wide_wait(D)) : "memory");
-    if (decltype(rows_tag)::value && has_next) wide_rows<MODE>(a, nxt, lane, wave, next_ids);
+    if (decltype(rows_tag)::value && has_next) {
+      // the lane index re-derived and made opaque here: the look-up addresses are
+      // then worked out on the spot instead of ahead of the item (where they would
+      // be spilled, and their reload would wait for every outstanding load)
+      int lane_here;
+      asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane_here));
+      wide_rows<MODE>(a, nxt, lane_here, wave, next_ids);
+    }
     if (IW) load_w(Tag<(SET + kWideWLead) % WS>{}, st + kWideWLead);
     if (IT) wide_fetch(rsrc, src, st + kWideTLead, wave, ring);
     const unsigned char* base = ring + (st % kWideStages) * kWideStage;
@@ -1081,7 +1089,8 @@ __global__ __launch_bounds__(kWideThreads, 1) void ffn_wide_kernel(FfnArgs a, Ex
   int local = blockIdx.x >> 3;
   const TileOrder order = tile_order(total, xcd, a.interleave && (plan.sizes & (plan.sizes - 1)) != 0);
   if (local >= order.count) return;
-  const int lane = threadIdx.x & (MOE_WAVE - 1), wave = threadIdx.x / MOE_WAVE;
+  const int lane = threadIdx.x & (MOE_WAVE - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE);   // uniform: a scalar register
 
   TileItem it = tile_item<kWideRows>(groups, plan, order.item(local), slabs);
   const ActRsrc rsrc = wide_resource(a, act_rows);
