@@ -1,0 +1,62 @@
+"""Host logic: which FFN kernel the library picks for the shapes the bench runs
+(no GPU needed: moe_ffn_kernel_name only evaluates the selection rules)."""
+import pytest
+
+from workloads import get_config
+
+
+@pytest.fixture(scope="module")
+def B():
+    import os
+    for v in ("MOE_TUNE_BLOCK", "MOE_TUNE_GU", "MOE_TUNE_DOWN", "MOE_TUNE_WIDE"):
+        assert v not in os.environ, f"{v} overrides the rules this test checks"
+    from paper_2509_23638_amd.build import LIB, build
+    if not os.path.exists(LIB):
+        build(verbose=False)
+    import paper_2509_23638_amd.binding as B
+    return B
+
+
+def _names(B, cfg, T=None):
+    sh = B.make_shape(T if T is not None else cfg.T, cfg.H, cfg.E, cfg.k, cfg.F, cfg.S, cfg.dtype, "tiled")
+    n = cfg.E + cfg.S
+    return B.moe_ffn_kernel_name(sh, 0, n), B.moe_ffn_kernel_name(sh, 1, n)
+
+
+def test_mixtral_decode_sizes(B):
+    cfg = get_config("c2_mixtral")
+    # wide experts: the persistent tiled kernel streams gate/up at every decode batch
+    assert _names(B, cfg, 64) == ("ffn_tile_kernel<gate/up>", "ffn_stream_kernel<down, halved contraction>")
+    assert _names(B, cfg, 1) == ("ffn_tile_kernel<gate/up>", "ffn_down_splitk_kernel")
+    assert _names(B, cfg, 8) == ("ffn_tile_kernel<gate/up>", "ffn_down_splitk_kernel")
+    # from about 24 rows per expert both phases are tiled, from 96 in the eight-wave form
+    assert _names(B, cfg, 256) == ("ffn_tile_kernel<gate/up>", "ffn_tile_kernel<down>")
+    assert _names(B, cfg, 512) == ("ffn_wide_kernel<gate/up>", "ffn_wide_kernel<down>")
+
+
+def test_fine_grained_and_prefill(B):
+    assert _names(B, get_config("c3_finegrained")) == (
+        "ffn_stream_kernel<gate/up, 64 rows>", "ffn_stream_kernel<down, 64 rows>")
+    assert _names(B, get_config("c4_dsv2lite_prefill")) == (
+        "ffn_wide_kernel<gate/up>", "ffn_wide_kernel<down>")
+    # many experts with a few rows each: enough workgroups without split-K
+    assert _names(B, get_config("c6_qwen3_a3b")) == (
+        "ffn_stream_kernel<gate/up, 64 rows>", "ffn_stream_kernel<down, halved contraction>")
+
+
+def test_choice_does_not_depend_on_the_number_of_listed_experts_once_blocks_are_filled(B):
+    """The streamed path calls the FFN over subsets of experts; with well-filled
+    blocks every such call must land on the same kernels as the all-resident
+    call (the eight-wave form is chosen from the shape alone)."""
+    cfg = get_config("c4_dsv2lite_prefill")
+    sh = B.make_shape(cfg.T, cfg.H, cfg.E, cfg.k, cfg.F, cfg.S, cfg.dtype, "tiled")
+    for phase in (0, 1):
+        names = {B.moe_ffn_kernel_name(sh, phase, n) for n in (1, 2, 7, 33, cfg.E + cfg.S)}
+        assert len(names) == 1, names
+
+
+def test_f32_storage_has_its_own_kernel(B):
+    cfg = get_config("c1_tiny")
+    sh = B.make_shape(cfg.T, cfg.H, cfg.E, cfg.k, cfg.F, cfg.S, "f32", "row_major")
+    assert B.moe_ffn_kernel_name(sh, 0, cfg.E) == "ffn_f32_kernel<gate/up>"
+    assert B.moe_ffn_kernel_name(sh, 1, cfg.E) == "ffn_f32_kernel<down>"
