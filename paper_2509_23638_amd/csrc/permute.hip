@@ -7,28 +7,27 @@
 // A = T*k flat assignment ids (a few tens of KB, L2-resident), counting with
 // ballots how many name an expert below e (that is offset[e]) and how many
 // name e (count[e]); a second scan writes perm / inv_perm for the ids that
-// name e.  Each of the four wavefronts owns a contiguous quarter of the ids,
-// so ranks ascend with the id and the order inside a bucket is stable.  All
-// integer work: the result is unique and bit-exact.
+// name e.  Each wavefront (four, or sixteen from 4096 ids) owns a contiguous
+// share of the ids, so ranks ascend with the id and the order inside a bucket
+// is stable.  All integer work: the result is unique and bit-exact.
 #include "common.h"
 
 namespace moe {
 namespace {
 
-constexpr int kPermWaves = 4;
-constexpr int kPermThreads = kPermWaves * MOE_WAVE;
+constexpr int kPermMaxWaves = 16;
 constexpr int kPermUnroll = 16;
 
-__global__ __launch_bounds__(kPermThreads) void permute_kernel(
+__global__ __launch_bounds__(kPermMaxWaves * MOE_WAVE) void permute_kernel(
     const int32_t* __restrict__ topk_idx, int32_t* __restrict__ count,
     int32_t* __restrict__ offset, int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm,
     int A, int E) {
-  __shared__ int s_eq[kPermWaves], s_less[kPermWaves];
+  __shared__ int s_eq[kPermMaxWaves], s_less[kPermMaxWaves];
   const int e = blockIdx.x;
   const int lane = threadIdx.x & (MOE_WAVE - 1);
-  const int wave = threadIdx.x / MOE_WAVE;
-  // quarter of the ids owned by this wave, a multiple of the wave width
-  const int per = ((A + kPermWaves - 1) / kPermWaves + MOE_WAVE - 1) / MOE_WAVE * MOE_WAVE;
+  const int wave = threadIdx.x / MOE_WAVE, n_waves = blockDim.x / MOE_WAVE;
+  // share of the ids owned by this wave, a multiple of the wave width
+  const int per = ((A + n_waves - 1) / n_waves + MOE_WAVE - 1) / MOE_WAVE * MOE_WAVE;
   const int lo = min(wave * per, A), hi = min(lo + per, A);   // lo == hi: nothing to scan
 
   // kPermUnroll independent loads are issued before any of them is used, so a
@@ -53,13 +52,13 @@ __global__ __launch_bounds__(kPermThreads) void permute_kernel(
     s_less[wave] = less;
   }
   __syncthreads();
-  int start = 0, total = 0;  // bucket start; ids naming e in earlier quarters
-  for (int w = 0; w < kPermWaves; ++w) {
+  int start = 0, total = 0, n = 0;  // bucket start; ids naming e in earlier shares; bucket size
+  for (int w = 0; w < n_waves; ++w) {
     start += s_less[w];
     if (w < wave) total += s_eq[w];
+    n += s_eq[w];
   }
   if (threadIdx.x == 0) {
-    const int n = s_eq[0] + s_eq[1] + s_eq[2] + s_eq[3];
     count[e] = n;
     offset[e] = start;
     if (e == E - 1) offset[E] = start + n;
@@ -94,7 +93,9 @@ __global__ __launch_bounds__(kPermThreads) void permute_kernel(
 moe_status launch_permute(const moe_shape& s, const int32_t* topk_idx, int32_t* count,
                           int32_t* offset, int32_t* perm, int32_t* inv_perm,
                           hipStream_t stream) {
-  hipLaunchKernelGGL(permute_kernel, dim3(s.E), dim3(kPermThreads), 0, stream, topk_idx, count,
+  // a scan is one memory round trip per 1024 ids and wave: more waves for long lists
+  const int waves = s.T * s.k >= 4096 ? kPermMaxWaves : 4;
+  hipLaunchKernelGGL(permute_kernel, dim3(s.E), dim3(waves * MOE_WAVE), 0, stream, topk_idx, count,
                      offset, perm, inv_perm, s.T * s.k, s.E);
   MOE_HIP(hipGetLastError());
   return MOE_OK;
