@@ -554,3 +554,37 @@ def test_layer_forward_random_shapes(B):
         assert err <= TOL["bf16"], what
         worst = max(worst, err)
     assert worst > 0.0
+
+
+def test_layer_forward_random_filled_shapes(B):
+    """The same kind of sweep over shapes with well-filled blocks (about a
+    hundred or more rows per expert, long enough contractions): the eight-wave
+    tiled kernels with every pipeline remainder, split and partly filled
+    blocks, shared experts, both layouts."""
+    r = np.random.Generator(np.random.PCG64(4052))
+    seen = set()
+    for i in range(12):
+        E = int(r.choice([1, 2, 3, 4, 6]))
+        k = int(r.integers(1, min(E, 3) + 1))
+        S = int(r.choice([0, 1, 2]))
+        T = int(r.choice([230, 300, 411, 520, 700]))
+        H = int(r.choice([512, 768, 1024]))
+        F = int(r.choice([512, 640, 768, 896, 1152]))
+        while T * (E + S) * F * H > 3e9:
+            T = T * 2 // 3
+        layout = str(r.choice(LAYOUTS))
+        cfg = _small(f"filled{i}", T=T, E=E, k=k, S=S, H=H, F=F, seed=700 + i,
+                     bias=str(r.choice(["none", "normal", "zipf"])), bias_scale=0.8)
+        L = make_layer(cfg)
+        ref = O.moe_layer(L["X"], L["Wr"], L["b"], L["Wg"], L["Wu"], L["Wd"], cfg.k, cfg.S)
+        if E > 1 and O.routing_margins(ref["logits"], cfg.k).min() <= 1e-9:
+            continue
+        sh = _shape(B, cfg, layout=layout)
+        seen.update(B.moe_ffn_kernel_name(sh, ph, cfg.E + cfg.S) for ph in (0, 1))
+        got = _layer_gpu(B, cfg, L, layout=layout)
+        what = f"case {i}: {cfg} {layout}"
+        assert np.array_equal(got["topk_idx"], ref["topk_idx"]), what
+        assert np.abs(got["topk_w"] - ref["topk_w"]).max() <= 1e-5, what
+        assert row_rel_err(got["out"], ref["out"]) <= TOL["bf16"], what
+    assert {"ffn_wide_kernel<gate/up>", "ffn_wide_kernel<down>"} <= seen, seen
+
