@@ -589,6 +589,38 @@ def test_layer_forward_random_filled_shapes(B):
     assert {"ffn_wide_kernel<gate/up>", "ffn_wide_kernel<down>"} <= seen, seen
 
 
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("case", [
+    dict(T=40, E=8, k=2, H=256, F=512),             # decode sizes, six experts without a token
+    dict(T=700, E=8, k=2, S=1, H=512, F=640),       # two buckets of 700 rows: three row blocks each
+    dict(T=300, E=4, k=1, H=768, F=768),            # one expert takes every token
+    dict(T=130, E=60, k=4, S=2, H=128, F=256),      # many experts, four in use
+], ids=lambda c: f"T{c['T']}_E{c['E']}_k{c['k']}")
+def test_layer_forward_every_token_to_the_same_experts(B, case, layout):
+    """The most skewed routing there is: a router bias far above the logits
+    sends every token to the same k experts, every other bucket is empty and
+    the used ones hold T rows each (several row blocks at the larger sizes)."""
+    cfg = _small("same_experts", seed=81, bias="none", **case)
+    L = make_layer(cfg)
+    b = np.zeros(cfg.E, dtype=np.float32)
+    chosen = [(3 * j + 1) % cfg.E for j in range(cfg.k)]
+    assert len(set(chosen)) == cfg.k
+    for j, e in enumerate(chosen):
+        b[e] = 40.0 + 0.75 * j
+    L["b"] = b
+    ref = O.moe_layer(L["X"], L["Wr"], L["b"], L["Wg"], L["Wu"], L["Wd"], cfg.k, cfg.S)
+    assert (np.sort(ref["topk_idx"], axis=1) == np.sort(chosen)).all()
+    if cfg.E > cfg.k:
+        assert O.routing_margins(ref["logits"], cfg.k).min() > 1e-6
+    got = _layer_gpu(B, cfg, L, layout=layout)
+    assert np.array_equal(got["topk_idx"], ref["topk_idx"])
+    assert np.abs(got["topk_w"] - ref["topk_w"]).max() <= 1e-5
+    count = np.zeros(cfg.E, dtype=np.int64)
+    count[chosen] = cfg.T
+    assert np.array_equal(got["count"], count)
+    assert row_rel_err(got["out"], ref["out"]) <= TOL["bf16"]
+
+
 @pytest.mark.parametrize("name", ["c2_mixtral", "c4_dsv2lite_prefill"])
 def test_repeated_forwards_are_bit_identical(B, name):
     """Same inputs, same bits, run after run: the persistent kernels hand ring
