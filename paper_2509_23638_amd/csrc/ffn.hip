@@ -450,7 +450,8 @@ __device__ __forceinline__ int tile_read_offset(int r, int c) {
 // times one slab of its weight rows.
 struct TileItem {
   int e, r0, row_end, slab;
-  bool single;   // the expert's bucket is this one block
+  int single;    // 1: the expert's bucket is this one block (an int: padding bytes made every copy of the
+                 // struct go through scratch memory, and the reload waited for every outstanding fetch)
 };
 
 template <int ROWS = 256>
