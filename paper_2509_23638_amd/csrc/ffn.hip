@@ -35,6 +35,9 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+using ActRsrc = __amdgpu_buffer_rsrc_t;   // buffer resource: base, size, range-checked 32-bit offsets
 
 constexpr int kWaves = 4;           // wavefronts per workgroup
 constexpr int kThreads = kWaves * MOE_WAVE;
@@ -504,10 +507,14 @@ __device__ __forceinline__ void tile_rows(const FfnArgs& a, const TileItem& it, 
 
 // Second half: the twelve source pointers of this lane (stage 0).
 // (NQ = 12; the weights-in-registers form below asks for the token sources only, NQ = 8.)
-template <int MODE, int NQ>
+// SAME_ROWS: the item covers the same row block as the one whose pointers are
+// in `cur` (another slab of its weights): the token pointers are taken over,
+// no look-up result is touched.
+template <int MODE, int NQ, bool SAME_ROWS = false>
 __device__ __forceinline__ void tile_sources(const FfnArgs& a, const ExpertTable& tab,
                                              const TileItem& it, const int (&ids)[8], int lane,
-                                             int wave, const uint16_t* (&src)[NQ]) {
+                                             int wave, const uint16_t* (&src)[NQ],
+                                             const uint16_t* const* cur = nullptr) {
   const int e = it.e;
   const int n0 = it.slab * (MODE == kGateUp ? 64 : 128);
   const int chunk = tile_fetch_chunk(lane);
@@ -515,6 +522,10 @@ __device__ __forceinline__ void tile_sources(const FfnArgs& a, const ExpertTable
   for (int q = 0; q < NQ; ++q) {
     const int h = wave + 4 * q, blk = h >> 1, u = h & 1;
     const int rr = tile_fetch_row(lane, u);   // row inside the 16-row block
+    if (q < 8 && SAME_ROWS) {
+      src[q] = cur[q];
+      continue;
+    }
     if (q < 8) {
       const int p = min(it.r0 + blk * 16 + rr, it.row_end - 1);   // bucket position
       int row = p;                                                 // down: h is in bucket order
@@ -796,6 +807,319 @@ __global__ __launch_bounds__(kThreads, 1) void ffn_tile_kernel(FfnArgs a, Expert
 }
 
 
+// ----------------------------------- tiled kernel, at most 64 tokens ----
+constexpr int kSmallNJ = 2;   // token tiles per wave: blocks of at most 64 rows
+
+// Issue this wave's fetches of an item's stage st into ring buffer `slot`: the
+// first NTOK of its eight token fetches (token blocks 0 .. 2 NTOK - 1 of the
+// sixteen) and its four weight fetches.  A source pointer advances 64 elements
+// along its row per stage, or two KiB tiles for tiled weights.
+template <int NTOK>
+__device__ __forceinline__ void tile_fetch_slot(const uint16_t* const (&src)[kFetchPerWave], int st,
+                                           int slot, int w_adv, int wave, unsigned char* ring) {
+  unsigned char* base = ring + slot * kTileStage;
+#pragma unroll
+  for (int q = 0; q < kFetchPerWave; ++q) {
+    if (q >= NTOK && q < 8) continue;
+    // weights are read once: marked non-temporal, so that they do not push the
+    // token rows (re-read by every slab of a block) out of L2
+    if (q >= 8)
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(src[q] + (size_t)st * w_adv),
+          (__attribute__((address_space(3))) void*)(base + (wave + 4 * q) * kFragBytes), 16, 0, 2);
+    else
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(src[q] + (size_t)st * kTileK),
+          (__attribute__((address_space(3))) void*)(base + (wave + 4 * q) * kFragBytes), 16, 0, 0);
+  }
+}
+
+__device__ __forceinline__ int tile_slot_after(int slot, int n) { return (slot + n) % kTileStages; }
+
+// One item.  On entry the fetches of its stages 0 and 1 are in flight (issued
+// by the previous item, or by the kernel's preamble).  The ring does not drain
+// between items: during its own last two stages an item issues the first two
+// stages of the workgroup's next item into the buffers that fall free, exactly
+// where a longer contraction would have put its stages ns and ns + 1; the next
+// item starts at ring position `slot0` + ns.
+// Result stores a wave issues per item: every wave issues all of them, rows past
+// the bucket's end are dropped by the buffer resource's range check, so the
+// number is a constant of the variant and the hand-written waits can count them.
+template <int MODE>
+constexpr int small_stores() { return kSmallNJ * (MODE == kGateUp ? 2 : 4); }
+
+// s_waitcnt vmcnt(n) for a wave-uniform run-time n (rounded down to an even
+// number: waiting for more is always safe), then the bare barrier.
+template <int C>
+__device__ __forceinline__ void small_wait_even(int half) {
+  if (half >= C) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(2 * C) : "memory");
+  else if constexpr (C > 0) small_wait_even<C - 1>(half);
+}
+__device__ __forceinline__ void small_wait_barrier(int n) { small_wait_even<24>(n >> 1); }
+
+// `older_stores` = result stores of the previous item that this wave issued
+// behind the fetches of stages 0 and 1 (0 for a workgroup's first item).
+template <int MODE>
+__device__ __forceinline__ void ffn_small_block(const FfnArgs& a, const ExpertTable& tab,
+                                               const TileItem& it, bool has_next,
+                                               const TileItem& nxt,
+                                               const uint16_t* (&src)[kFetchPerWave],
+                                               unsigned char* ring, int older_stores, int slot0) {
+  constexpr int NJ = kSmallNJ;
+  const int r0 = it.r0, row_end = it.row_end;
+  const int lane = threadIdx.x & (MOE_WAVE - 1), wave = threadIdx.x / MOE_WAVE;
+  const int wm = wave & 1, wn = wave >> 1;
+  const int n0 = it.slab * (MODE == kGateUp ? 64 : 128);
+  const int w_adv = a.tiled ? 1024 : kTileK;
+  // where lane (r, g) finds row r, chunk 4 s + g of a block, for k-step s = 0, 1
+  int rd[2];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) rd[ks] = tile_read_offset(lane & 15, 4 * ks + (lane >> 4));
+  // tiled weights arrive as whole MFMA tiles: k-step ks is the ks-th KiB of the block
+  int rdw[2];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) rdw[ks] = a.tiled ? ks * kFragBytes + lane * 16 : rd[ks];
+
+  f32x4 acc[4][NJ];   // this wave's token tiles are wm, wm + 2, ...
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  int next_ids[8];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) next_ids[q] = 0;
+
+  // One stage's arithmetic on the ring buffer at byte offset `slot_bytes`.  The
+  // operand reads are written as instructions, not as loads through a pointer:
+  // seeing a read of the ring, the compiler protects it from the direct-to-LDS
+  // fetches in flight with a wait for ALL of them wherever control flow has
+  // merged (after the run-time wait selection, after the next item's set-up)
+  // -- the ring's own discipline (wait, barrier, buffer freed a stage ago)
+  // already orders them.  All reads are issued, one wait, then the MFMAs in the
+  // same order as in the general kernel (same sums, same bits).
+  const uint32_t ring_lds =
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)ring;
+  uint32_t wofs[2], tofs[2];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+    wofs[ks] = ring_lds + rdw[ks] + (16 + wn * (MODE == kGateUp ? 2 : 4)) * kDblFrag;
+    tofs[ks] = ring_lds + rd[ks] + wm * kDblFrag;
+  }
+  auto multiply = [&](int slot_bytes) {
+    bf16x8 wf[2][4], tf[2][NJ];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const uint32_t wa = wofs[ks] + slot_bytes, ta = tofs[ks] + slot_bytes;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        // gate/up: blocks 16 + (i >> 1) * 4 + wn * 2 + (i & 1); down: 16 + wn * 4 + i
+        if (MODE == kGateUp)
+          asm volatile("ds_read_b128 %0, %1 offset:%2"
+                       : "=v"(wf[ks][i])
+                       : "v"(wa), "n"(((i >> 1) * 4 + (i & 1)) * kDblFrag));
+        else
+          asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(wf[ks][i]) : "v"(wa), "n"(i * kDblFrag));
+      }
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(tf[ks][j]) : "v"(ta), "n"(2 * j * kDblFrag));
+    }
+    static_assert(NJ == 2, "the wait below names every operand register");
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(wf[0][0]), "+v"(wf[0][1]), "+v"(wf[0][2]), "+v"(wf[0][3]), "+v"(wf[1][0]),
+                   "+v"(wf[1][1]), "+v"(wf[1][2]), "+v"(wf[1][3]), "+v"(tf[0][0]), "+v"(tf[0][1]),
+                   "+v"(tf[1][0]), "+v"(tf[1][1]));
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ks][i], tf[ks][j], acc[i][j], 0, 0, 0);
+  };
+
+  // D layout: lane holds rows 4*g .. 4*g+3 of the 16-row weight tile, column r = token.
+  // The stores go through a buffer resource that covers this block's rows of the
+  // output and nothing else: a row past the bucket's end is out of its range and
+  // the hardware drops the store, so every wave issues the same number of stores.
+  const int block_rows = __builtin_amdgcn_readfirstlane(min(row_end - r0, kTileRows));
+  const size_t out_elt = MODE == kGateUp ? 2 : 4;
+  const size_t block_base = (size_t)__builtin_amdgcn_readfirstlane(r0) * a.N * out_elt;
+  const ActRsrc out_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      static_cast<unsigned char*>(a.out) + block_base, 0, (int)(block_rows * a.N * out_elt), 0x00020000);
+  auto epilogue = [&]() {
+    const int r = lane & 15, g = lane >> 4;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int row = (wm + 2 * j) * 16 + r;   // inside the block
+      if (MODE == kGateUp) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          float hv[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) hv[q] = silu_f(acc[i][j][q]) * acc[2 + i][j][q];
+          u32x2 pk;
+          pk[0] = pack_bf16x2(hv[0], hv[1]);
+          pk[1] = pack_bf16x2(hv[2], hv[3]);
+          __builtin_amdgcn_raw_buffer_store_b64(
+              pk, out_rsrc, (int)((row * a.N + n0 + (wn * 2 + i) * 16 + 4 * g) * out_elt), 0, 0);
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          u32x4 v;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) v[q] = __float_as_uint(acc[i][j][q]);
+          __builtin_amdgcn_raw_buffer_store_b128(
+              v, out_rsrc, (int)((row * a.N + n0 + (wn * 4 + i) * 16 + 4 * g) * out_elt), 0, 0);
+        }
+      }
+    }
+  };
+
+  // Every stage starts with a wait and a barrier: this wave's fetches of stage
+  // st have landed once at most the operations issued after them are still
+  // outstanding (loads complete in order).  A bare barrier, not
+  // __syncthreads(): the fence that comes with the latter makes the compiler
+  // wait for EVERY outstanding fetch (the ones of the next stages too), which
+  // would put the whole ring one stage deep.  What the barrier has to order is
+  // covered by hand: the vmcnt wait above it (this wave's direct-to-LDS fetches
+  // of stage st have been written), and program order (a wave's LDS reads of
+  // stage st-1 fed MFMAs it has already issued).  What is younger than stage
+  // st's fetches at its wait:
+  //   stage 0:      stage 1 (fetched in full, twelve per wave) and the previous
+  //                 item's result stores -- loads and stores share the one
+  //                 in-order counter, and a store is acknowledged long after a
+  //                 load of the same age has landed, so they are counted, not
+  //                 waited for;
+  //   stage 1:      those stores and stage 2 (NJ + 4 fetches: only the token
+  //                 blocks this item multiplies);
+  //   last stage:   the next item's stage 0 (twelve), if there is a next item;
+  //   other stages: the following stage, NJ + 4 (the row look-ups or the stores
+  //                 in between only make the wait conservative).
+  const int ns = a.K / kTileK;
+  const uint16_t* next_src[kFetchPerWave];
+  const bool same_rows = has_next && nxt.e == it.e && nxt.r0 == it.r0;
+  int slot = slot0;   // ring buffer of the stage at hand
+  auto stage_base = [&]() {
+    const int bytes = slot * kTileStage;
+    slot = tile_slot_after(slot, 1);
+    return bytes;
+  };
+  if (ns >= 4) {
+    small_wait_barrier(kFetchPerWave + older_stores);
+    tile_fetch_slot<NJ>(src, 2, tile_slot_after(slot, 2), w_adv, wave, ring);
+    multiply(stage_base());
+    small_wait_barrier(NJ + 4 + older_stores);
+    tile_fetch_slot<NJ>(src, 3, tile_slot_after(slot, 2), w_adv, wave, ring);
+    multiply(stage_base());
+    for (int st = 2; st < ns - 2; ++st) {
+      asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(NJ + 4) : "memory");
+      tile_fetch_slot<NJ>(src, st + 2, tile_slot_after(slot, 2), w_adv, wave, ring);   // into the buffer stage st-1 used
+      multiply(stage_base());
+    }
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(NJ + 4) : "memory");
+    // (Both paths are written out to the end: behind the join of a conditional
+    // the compiler would first wait for every outstanding fetch.)
+    if (has_next) {
+      // The next item's first two stages, in full (its size is not a constant
+      // here).  If it is another slab of the same row block, its pointers need
+      // no look-up result: otherwise the first use of one makes the compiler
+      // wait for everything outstanding (it cannot count past direct-to-LDS
+      // fetches), stage ns - 1 included.
+      // (Nor are the look-ups issued early for the other case: a load the
+      // compiler has to assume pending on some path makes it wait for
+      // everything outstanding at the first reuse of a register of theirs.)
+      if (same_rows) {
+        tile_sources<MODE, kFetchPerWave, true>(a, tab, nxt, next_ids, lane, wave, next_src, src);
+      } else {
+        tile_rows<MODE>(a, nxt, lane, wave, next_ids);
+        tile_sources<MODE, kFetchPerWave>(a, tab, nxt, next_ids, lane, wave, next_src);
+      }
+      tile_fetch_slot<8>(next_src, 0, tile_slot_after(slot, 2), w_adv, wave, ring);
+      multiply(stage_base());
+      asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(kFetchPerWave) : "memory");
+      tile_fetch_slot<8>(next_src, 1, tile_slot_after(slot, 2), w_adv, wave, ring);
+      multiply(stage_base());
+      epilogue();
+#pragma unroll
+      for (int q = 0; q < kFetchPerWave; ++q) src[q] = next_src[q];
+    } else {
+      multiply(stage_base());
+      asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+      multiply(stage_base());
+      epilogue();
+    }
+    return;
+  }
+
+  // Contractions of fewer than four stages: the simple hand-over (the next
+  // item's first fetches are issued after the last stage).
+  for (int st = 0; st < ns; ++st) {
+    if (st + 1 >= ns) asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    else if (st == 0) small_wait_barrier(kFetchPerWave + older_stores);
+    else small_wait_barrier(NJ + 4 + older_stores);
+    if (st + 2 < ns) tile_fetch_slot<NJ>(src, st + 2, tile_slot_after(slot, 2), w_adv, wave, ring);
+    multiply(stage_base());
+  }
+  if (has_next) {
+    tile_rows<MODE>(a, nxt, lane, wave, next_ids);
+    tile_sources<MODE, kFetchPerWave>(a, tab, nxt, next_ids, lane, wave, next_src);
+    asm volatile("s_barrier" ::: "memory");
+    tile_fetch_slot<8>(next_src, 0, slot, w_adv, wave, ring);
+    if (ns > 1) tile_fetch_slot<8>(next_src, 1, tile_slot_after(slot, 1), w_adv, wave, ring);
+    epilogue();
+#pragma unroll
+    for (int q = 0; q < kFetchPerWave; ++q) src[q] = next_src[q];
+  } else {
+    epilogue();
+  }
+}
+
+// Launches of at most 64 tokens: no bucket, a shared expert's included, holds
+// more than 64 rows, so every block is the smallest variant (two token tiles
+// per wave).  A kernel of its own, so that the longer live ranges of the
+// continuous ring meet that variant's register budget and not the largest one's.
+template <int MODE>
+__global__ __launch_bounds__(kThreads, 1) void ffn_tile_small_kernel(FfnArgs a, ExpertTable tab,
+                                                                     GroupList groups) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char ring[];
+  __shared__ TilePlan plan;
+  tile_plan_build(plan, a, groups);
+  const int slabs = a.N / (MODE == kGateUp ? 64 : 128);
+  const int total = plan.first[groups.n] * slabs;
+  const int xcd = blockIdx.x & 7, stride = gridDim.x >> 3;   // grid is a multiple of 8
+  int local = blockIdx.x >> 3;
+  const TileOrder order = tile_order(total, xcd, a.interleave && (plan.sizes & (plan.sizes - 1)) != 0);
+  if (local >= order.count) return;
+  const int lane = threadIdx.x & (MOE_WAVE - 1), wave = threadIdx.x / MOE_WAVE;
+  const int w_adv = a.tiled ? 1024 : kTileK;
+
+  TileItem it = tile_item(groups, plan, order.item(local), slabs);
+  const uint16_t* src[kFetchPerWave];
+  {
+    int rows[8];
+    tile_rows<MODE>(a, it, lane, wave, rows);
+    tile_sources<MODE, kFetchPerWave>(a, tab, it, rows, lane, wave, src);
+    tile_fetch_slot<8>(src, 0, 0, w_adv, wave, ring);
+    if (a.K / kTileK > 1) tile_fetch_slot<8>(src, 1, 1, w_adv, wave, ring);
+  }
+  int slot0 = 0;          // ring buffer of the current item's stage 0
+  int older_stores = 0;   // result stores of the previous item, issued behind this item's first fetches
+  while (true) {
+    const bool has_next = local + stride < order.count;
+    TileItem nxt = it;
+    if (has_next) nxt = tile_item(groups, plan, order.item(local + stride), slabs);
+    ffn_small_block<MODE>(a, tab, it, has_next, nxt, src, ring, older_stores, slot0);
+    older_stores = small_stores<MODE>();
+    if (!has_next) break;
+    slot0 = tile_slot_after(slot0, a.K / kTileK);
+    it = nxt;
+    local += stride;
+  }
+}
+
 // ------------------------------------- prefill: weights in registers ----
 // A second form of the tiled kernel for well-filled blocks (many rows per
 // expert).  Two measurements shape it.  A wavefront that is alone on its SIMD
@@ -843,8 +1167,6 @@ constexpr int wide_wait(int d) {
 // buffer instruction among the ordinary loads, so its own waits for the weight
 // registers come out exact.  (Behind a direct-to-LDS load in the flat-address
 // encoding it waits for every outstanding load instead.)
-using ActRsrc = __amdgpu_buffer_rsrc_t;
-
 __device__ __forceinline__ ActRsrc wide_resource(const FfnArgs& a, long long act_rows) {
   // out-of-range reads return zero; the launcher keeps the matrix under 2 GiB
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.act), 0,
@@ -1181,6 +1503,8 @@ moe_status launch_tile(const moe_shape& s, const FfnArgs& args, const ExpertTabl
   if (!attr_set) {
     MOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_tile_kernel<MODE>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kTileLds));
+    MOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_tile_small_kernel<MODE>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kTileLds));
     for (int r = 0; r < kWideWeightSets; ++r)
       MOE_HIP(hipFuncSetAttribute(WideKernels<MODE>::get(r),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, kWideLds));
@@ -1205,8 +1529,12 @@ moe_status launch_tile(const moe_shape& s, const FfnArgs& args, const ExpertTabl
     MOE_HIP(hipLaunchKernel(WideKernels<MODE>::get(r), dim3(grid), dim3(kWideThreads), params,
                             kWideLds, stream));
   } else {
-    hipLaunchKernelGGL((ffn_tile_kernel<MODE>), dim3(grid), dim3(kThreads), kTileLds, stream, args,
-                       tab, groups);
+    if (s.T <= 64)   // every bucket, a shared expert's too, has at most T rows
+      hipLaunchKernelGGL((ffn_tile_small_kernel<MODE>), dim3(grid), dim3(kThreads), kTileLds, stream,
+                         args, tab, groups);
+    else
+      hipLaunchKernelGGL((ffn_tile_kernel<MODE>), dim3(grid), dim3(kThreads), kTileLds, stream, args,
+                         tab, groups);
   }
   MOE_HIP(hipGetLastError());
   return MOE_OK;
@@ -1580,6 +1908,7 @@ const char* ffn_kernel_name(const moe_shape& s, int phase, int n_groups) {
   switch (v) {
     case kTile:
       if (wide_form(s, phase)) return phase == 0 ? "ffn_wide_kernel<gate/up>" : "ffn_wide_kernel<down>";
+      if (s.T <= 64) return phase == 0 ? "ffn_tile_small_kernel<gate/up>" : "ffn_tile_small_kernel<down>";
       return phase == 0 ? "ffn_tile_kernel<gate/up>" : "ffn_tile_kernel<down>";
     case kSplitK: return "ffn_down_splitk_kernel";
     case kHalves: return "ffn_stream_kernel<down, halved contraction>";

@@ -82,6 +82,10 @@ SMALL = [
     # (contraction lengths of 8, 10 and 12 stages), uneven and split blocks
     _small("s_bf16_filled_blocks", T=400, E=4, k=2, H=512, F=640, S=1, bias="zipf", bias_scale=0.7),
     _small("s_bf16_filled_blocks_12", T=300, E=2, k=1, H=768, F=768, S=1),
+    # at most 64 tokens in the tiled kernels (both phases; the shortest contraction whose ring runs on
+    # from item to item, several items per workgroup; shared experts; one bucket nearly full)
+    _small("s_bf16_small_tiled", T=60, E=2, k=1, H=256, F=512),
+    _small("s_bf16_small_tiled_two_items", T=64, E=2, k=2, H=512, F=8192, S=1),
 ]
 
 
@@ -431,7 +435,8 @@ def test_small_configs_reach_every_ffn_kernel(B):
         sh = _shape(B, cfg, layout="tiled")
         for phase in (0, 1):
             seen.add(B.moe_ffn_kernel_name(sh, phase, cfg.E + cfg.S))
-    want = {"ffn_tile_kernel<gate/up>", "ffn_tile_kernel<down>", "ffn_wide_kernel<gate/up>",
+    want = {"ffn_tile_kernel<gate/up>", "ffn_tile_kernel<down>", "ffn_tile_small_kernel<gate/up>",
+            "ffn_tile_small_kernel<down>", "ffn_wide_kernel<gate/up>",
             "ffn_wide_kernel<down>", "ffn_down_splitk_kernel",
             "ffn_stream_kernel<down, halved contraction>", "ffn_stream_kernel<gate/up, 64 rows>",
             "ffn_stream_kernel<down, 64 rows>", "ffn_stream_kernel<gate/up, 128 rows>",
