@@ -988,14 +988,14 @@ __device__ __forceinline__ void ffn_small_block(const FfnArgs& a, const ExpertTa
   // of stage st have been written), and program order (a wave's LDS reads of
   // stage st-1 fed MFMAs it has already issued).  What is younger than stage
   // st's fetches at its wait:
-  //   stage 0:      stage 1 (fetched in full, twelve per wave) and the previous
-  //                 item's result stores -- loads and stores share the one
+  //   stage 0:      stage 1 (NJ + 4 fetches per wave, like every stage here) and
+  //                 the previous item's result stores -- loads and stores share the one
   //                 in-order counter, and a store is acknowledged long after a
   //                 load of the same age has landed, so they are counted, not
   //                 waited for;
   //   stage 1:      those stores and stage 2 (NJ + 4 fetches: only the token
   //                 blocks this item multiplies);
-  //   last stage:   the next item's stage 0 (twelve), if there is a next item;
+  //   last stage:   the next item's stage 0 (NJ + 4), if there is a next item;
   //   other stages: the following stage, NJ + 4 (the row look-ups or the stores
   //                 in between only make the wait conservative).
   const int ns = a.K / kTileK;
@@ -1008,7 +1008,7 @@ __device__ __forceinline__ void ffn_small_block(const FfnArgs& a, const ExpertTa
     return bytes;
   };
   if (ns >= 4) {
-    small_wait_barrier(kFetchPerWave + older_stores);
+    small_wait_barrier(NJ + 4 + older_stores);
     tile_fetch_slot<NJ>(src, 2, tile_slot_after(slot, 2), w_adv, wave, ring);
     multiply(stage_base());
     small_wait_barrier(NJ + 4 + older_stores);
@@ -1023,8 +1023,8 @@ __device__ __forceinline__ void ffn_small_block(const FfnArgs& a, const ExpertTa
     // (Both paths are written out to the end: behind the join of a conditional
     // the compiler would first wait for every outstanding fetch.)
     if (has_next) {
-      // The next item's first two stages, in full (its size is not a constant
-      // here).  If it is another slab of the same row block, its pointers need
+      // The next item's first two stages (every block of this kernel has the
+      // same size class).  If it is another slab of the same row block, its pointers need
       // no look-up result: otherwise the first use of one makes the compiler
       // wait for everything outstanding (it cannot count past direct-to-LDS
       // fetches), stage ns - 1 included.
@@ -1037,10 +1037,10 @@ __device__ __forceinline__ void ffn_small_block(const FfnArgs& a, const ExpertTa
         tile_rows<MODE>(a, nxt, lane, wave, next_ids);
         tile_sources<MODE, kFetchPerWave>(a, tab, nxt, next_ids, lane, wave, next_src);
       }
-      tile_fetch_slot<8>(next_src, 0, tile_slot_after(slot, 2), w_adv, wave, ring);
+      tile_fetch_slot<NJ>(next_src, 0, tile_slot_after(slot, 2), w_adv, wave, ring);
       multiply(stage_base());
-      asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(kFetchPerWave) : "memory");
-      tile_fetch_slot<8>(next_src, 1, tile_slot_after(slot, 2), w_adv, wave, ring);
+      asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(NJ + 4) : "memory");
+      tile_fetch_slot<NJ>(next_src, 1, tile_slot_after(slot, 2), w_adv, wave, ring);
       multiply(stage_base());
       epilogue();
 #pragma unroll
@@ -1058,7 +1058,7 @@ __device__ __forceinline__ void ffn_small_block(const FfnArgs& a, const ExpertTa
   // item's first fetches are issued after the last stage).
   for (int st = 0; st < ns; ++st) {
     if (st + 1 >= ns) asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-    else if (st == 0) small_wait_barrier(kFetchPerWave + older_stores);
+    else if (st == 0) small_wait_barrier(NJ + 4 + older_stores);
     else small_wait_barrier(NJ + 4 + older_stores);
     if (st + 2 < ns) tile_fetch_slot<NJ>(src, st + 2, tile_slot_after(slot, 2), w_adv, wave, ring);
     multiply(stage_base());
@@ -1067,8 +1067,8 @@ __device__ __forceinline__ void ffn_small_block(const FfnArgs& a, const ExpertTa
     tile_rows<MODE>(a, nxt, lane, wave, next_ids);
     tile_sources<MODE, kFetchPerWave>(a, tab, nxt, next_ids, lane, wave, next_src);
     asm volatile("s_barrier" ::: "memory");
-    tile_fetch_slot<8>(next_src, 0, slot, w_adv, wave, ring);
-    if (ns > 1) tile_fetch_slot<8>(next_src, 1, tile_slot_after(slot, 1), w_adv, wave, ring);
+    tile_fetch_slot<NJ>(next_src, 0, slot, w_adv, wave, ring);
+    if (ns > 1) tile_fetch_slot<NJ>(next_src, 1, tile_slot_after(slot, 1), w_adv, wave, ring);
     epilogue();
 #pragma unroll
     for (int q = 0; q < kFetchPerWave; ++q) src[q] = next_src[q];
@@ -1102,8 +1102,8 @@ __global__ __launch_bounds__(kThreads, 1) void ffn_tile_small_kernel(FfnArgs a, 
     int rows[8];
     tile_rows<MODE>(a, it, lane, wave, rows);
     tile_sources<MODE, kFetchPerWave>(a, tab, it, rows, lane, wave, src);
-    tile_fetch_slot<8>(src, 0, 0, w_adv, wave, ring);
-    if (a.K / kTileK > 1) tile_fetch_slot<8>(src, 1, 1, w_adv, wave, ring);
+    tile_fetch_slot<kSmallNJ>(src, 0, 0, w_adv, wave, ring);
+    if (a.K / kTileK > 1) tile_fetch_slot<kSmallNJ>(src, 1, 1, w_adv, wave, ring);
   }
   int slot0 = 0;          // ring buffer of the current item's stage 0
   int older_stores = 0;   // result stores of the previous item, issued behind this item's first fetches
