@@ -836,12 +836,6 @@ __device__ __forceinline__ void tile_fetch_slot(const uint16_t* const (&src)[kFe
 
 __device__ __forceinline__ int tile_slot_after(int slot, int n) { return (slot + n) % kTileStages; }
 
-// One item.  On entry the fetches of its stages 0 and 1 are in flight (issued
-// by the previous item, or by the kernel's preamble).  The ring does not drain
-// between items: during its own last two stages an item issues the first two
-// stages of the workgroup's next item into the buffers that fall free, exactly
-// where a longer contraction would have put its stages ns and ns + 1; the next
-// item starts at ring position `slot0` + ns.
 // Result stores a wave issues per item: every wave issues all of them, rows past
 // the bucket's end are dropped by the buffer resource's range check, so the
 // number is a constant of the variant and the hand-written waits can count them.
@@ -857,6 +851,12 @@ __device__ __forceinline__ void small_wait_even(int half) {
 }
 __device__ __forceinline__ void small_wait_barrier(int n) { small_wait_even<24>(n >> 1); }
 
+// One item.  On entry the fetches of its stages 0 and 1 are in flight (issued
+// by the previous item, or by the kernel's preamble).  The ring does not drain
+// between items: during its own last two stages an item issues the first two
+// stages of the workgroup's next item into the buffers that fall free, exactly
+// where a longer contraction would have put its stages ns and ns + 1; the next
+// item starts at ring position `slot0` + ns.
 // `older_stores` = result stores of the previous item that this wave issued
 // behind the fetches of stages 0 and 1 (0 for a workgroup's first item).
 template <int MODE>
