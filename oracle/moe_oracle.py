@@ -24,8 +24,11 @@ Readings taken where the paper is silent:
 Pins (tests/test_oracle_pins.py): closed-form softmax weights, rank-one
 closed-form FFN against pure-Python exact sums, brute-force subset top-k incl.
 crafted ties, k = E dense mixture, E = 1 plain FFN, bucket invariants,
-identity-expert round trip, linearity, shared-expert concatenation, and the
-expert sizes printed in Table 2.  No function here is "parity unpinned".
+identity-expert round trip, linearity, shared-expert concatenation, the expert
+sizes printed in Table 2, hand-worked routing margins (checked against the
+selector under perturbation), and a two-layer bf16 stack whose normalised
+inputs land on bf16 bit patterns worked by hand.  Planted mistakes in each of
+these functions fail their pins.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 

@@ -141,6 +141,56 @@ def check_router_logits_exact():
     assert np.array_equal(O.router_logits(X, Wr, None), lg - b.astype(np.float64))
 
 
+def check_routing_margins_hand_worked():
+    """The margin is the smallest gap between neighbours among the k+1 LARGEST
+    logits: gaps inside the top-k fix the output order, the gap between the
+    k-th and the (k+1)-th fixes membership; anything further down is irrelevant."""
+    rows = np.array([
+        [3.0, 1.0, 2.5, 0.0],      # sorted 3, 2.5, 1, 0
+        [5.0, 4.0, 3.9, 0.0],      # the k-th / (k+1)-th gap (0.1) is the small one at k = 2
+        [0.99, 5.0, 1.0, 3.0],     # unsorted; the tiny gap 1 - 0.99 sits below the top-2
+        [-1.0, -4.0, -1.5, -9.0],  # negative logits
+        [2.0, 1.0, 2.0, 0.0],      # exact tie inside the top-2
+    ])
+    m1 = O.routing_margins(rows, 1)
+    assert np.allclose(m1, [0.5, 1.0, 2.0, 0.5, 0.0], rtol=0, atol=1e-15)
+    m2 = O.routing_margins(rows, 2)
+    assert np.allclose(m2, [0.5, 0.1, 2.0, 0.5, 0.0], rtol=0, atol=1e-12)
+    assert m2[4] == 0.0
+    m3 = O.routing_margins(rows, 3)
+    assert np.allclose(m3, [0.5, 0.1, 0.01, 0.5, 0.0], rtol=0, atol=1e-12)
+    # k = E: only the gaps inside the list (there is no (k+1)-th logit)
+    m4 = O.routing_margins(rows, 4)
+    assert np.allclose(m4, [0.5, 0.1, 0.01, 0.5, 0.0], rtol=0, atol=1e-12)
+    # one expert: nothing to confuse
+    assert np.all(np.isinf(O.routing_margins(np.array([[0.3], [-2.0]]), 1)))
+    # a tie between the k-th and the (k+1)-th logit is a zero margin
+    assert O.routing_margins(np.array([[7.0, 1.0, 1.0, 0.0]]), 2)[0] == 0.0
+    assert O.routing_margins(np.array([[7.0, 1.0, 1.0, 0.0]]), 1)[0] == 6.0
+    # consistent with the selector: perturbing any logit by less than half the margin
+    # changes neither the selected experts nor their order
+    r = _rng(40)
+    for _ in range(40):
+        E = int(r.integers(2, 9))
+        k = int(r.integers(1, E + 1))
+        lg = r.standard_normal((1, E))
+        m = O.routing_margins(lg, k)[0]
+        assert m > 0
+        base = O.select_topk(lg[0], k).tolist()
+        for _ in range(8):
+            pert = lg[0] + r.uniform(-0.49, 0.49, size=E) * m
+            assert O.select_topk(pert, k).tolist() == base
+        # and a swap of the two logits that realise the margin does change it
+        s = np.argsort(-lg[0], kind="stable")
+        top = s[: min(k + 1, E)]
+        gaps = lg[0][top[:-1]] - lg[0][top[1:]]
+        j = int(np.argmin(gaps))
+        assert abs(gaps[j] - m) < 1e-15
+        sw = lg[0].copy()
+        sw[top[j]], sw[top[j + 1]] = sw[top[j + 1]], sw[top[j]]
+        assert O.select_topk(sw, k).tolist() != base
+
+
 # ----------------------------------------------------------------- expert --
 def _py_ffn(x, Wg, Wu, Wd):
     """SiLU-gated FFN with exactly rounded dot products (math.fsum), pure
@@ -359,9 +409,59 @@ def check_rmsnorm_and_stack():
         r = O.moe_layer(inp, L[i]["Wr"], L[i]["b"], L[i]["Wg"], L[i]["Wu"], L[i]["Wd"], 2)
         x = x + r["out"]
     assert np.array_equal(xf, x)
-    # bf16 storage: the layer input is a bf16 bit pattern of the normalised x
-    xb, tb = O.moe_stack(bf16_bits_from_f32(X0), L, k=2, storage="bf16")
-    assert tb[0]["inp"].dtype == np.uint16 and np.isfinite(xb).all()
+
+
+def check_stack_bf16_hand_worked():
+    """bf16 storage of the stack, two layers, values worked by hand.
+
+    Row 0 is +-1 everywhere: mean square 1, so the normalised row is
+    +-1/sqrt(1 + 1e-6) = +-0.9999995, which rounds to bf16 +-1.0 (0x3F80 /
+    0xBF80).  Row 1 alternates 3, 4: mean square 12.5; 3/sqrt(12.500001) =
+    0.848528 lies in [0.5, 1) where bf16 steps are 2^-8, 0.848528 * 256 = 217.22
+    -> 217/256 = 0.84765625 = 0x3F59; 4/sqrt(12.500001) = 1.131371 lies in
+    [1, 2) with steps 2^-7, 1.131371 * 128 = 144.82 -> 145/128 = 1.1328125 =
+    0x3F91.  The layer input must be exactly those bits; the residual stream
+    adds the block output to the UN-normalised float64 row."""
+    H, E, F, k = 4, 3, 5, 2
+    X0 = bf16_bits_from_f32(np.array([[1, -1, 1, -1], [3, 4, 3, 4]], dtype=np.float32))
+    want_bits = np.array([[0x3F80, 0xBF80, 0x3F80, 0xBF80], [0x3F59, 0x3F91, 0x3F59, 0x3F91]],
+                         dtype=np.uint16)
+    want_vals = [[1.0, -1.0, 1.0, -1.0], [217 / 256, 145 / 128, 217 / 256, 145 / 128]]
+    r = _rng(41)
+    bf = lambda a: bf16_bits_from_f32(a.astype(np.float32))
+    layers = [dict(Wr=bf(r.standard_normal((E, H))), b=r.standard_normal(E).astype(np.float32),
+                   Wg=bf(r.standard_normal((E, F, H)) * 0.5), Wu=bf(r.standard_normal((E, F, H)) * 0.5),
+                   Wd=bf(r.standard_normal((E, H, F)) * 0.5)) for _ in range(2)]
+    xf, trace = O.moe_stack(X0, layers, k=k, storage="bf16")
+    assert trace[0]["inp"].dtype == np.uint16
+    assert np.array_equal(trace[0]["inp"], want_bits)
+
+    # layer 0 by the pure-Python routines on the hand-worked input values
+    def py_layer(L, rows):
+        tolist = lambda a: O.widen(a).tolist()
+        outs = []
+        for x in rows:
+            lg = [float(L["b"][e]) + math.fsum(w * v for w, v in zip(tolist(L["Wr"][e]), x))
+                  for e in range(E)]
+            sel = _brute_topk(lg, k)
+            z = [math.exp(lg[e] - lg[sel[0]]) for e in sel]
+            w = [v / math.fsum(z) for v in z]
+            ys = [_py_ffn(x, tolist(L["Wg"][e]), tolist(L["Wu"][e]), tolist(L["Wd"][e])) for e in sel]
+            outs.append([math.fsum(w[j] * ys[j][o] for j in range(k)) for o in range(H)])
+        return np.array(outs)
+
+    out0 = py_layer(layers[0], want_vals)
+    assert np.allclose(trace[0]["out"], out0, rtol=1e-12, atol=1e-15)
+    x1 = np.array([[1.0, -1.0, 1.0, -1.0], [3.0, 4.0, 3.0, 4.0]]) + out0
+    # layer 1 sees bf16(rmsnorm(x1)): nearest bf16 neighbours checked with exact fractions
+    n1 = x1 / np.sqrt((x1 * x1).mean(axis=1, keepdims=True) + 1e-6)
+    got1 = O.widen(trace[1]["inp"])
+    for v, g in zip(n1.reshape(-1), got1.reshape(-1)):
+        ulp = 2.0 ** (math.floor(math.log2(abs(g))) - 7)
+        assert Fraction(g) % Fraction(ulp) == 0            # a bf16 value
+        assert abs(Fraction(v) - Fraction(g)) <= Fraction(ulp) / 2
+    out1 = py_layer(layers[1], got1.tolist())
+    assert np.allclose(xf, x1 + out1, rtol=1e-12, atol=1e-14)
 
 
 def check_prefetch_set():
@@ -449,7 +549,73 @@ def _m_softmax_selected_only_wrong(logit_row, idx):
     return z / z.sum()
 
 
+def _m_margins_topk_only(logits, k):
+    out = np.empty(logits.shape[0])
+    for t in range(logits.shape[0]):
+        s = np.sort(logits[t])[::-1][:k]
+        out[t] = np.min(s[:-1] - s[1:]) if s.shape[0] > 1 else np.inf
+    return out
+
+
+def _m_margins_all_gaps(logits, k):
+    s = np.sort(logits, axis=1)[:, ::-1]
+    return np.min(s[:, :-1] - s[:, 1:], axis=1) if logits.shape[1] > 1 else np.full(logits.shape[0], np.inf)
+
+
+def _m_margins_boundary_only(logits, k):
+    s = np.sort(logits, axis=1)[:, ::-1]
+    E = logits.shape[1]
+    return s[:, k - 1] - s[:, k] if k < E else np.full(logits.shape[0], np.inf)
+
+
+def _m_rmsnorm_no_eps(x, eps=1e-6):
+    x = np.asarray(x, dtype=np.float64)
+    return x / np.sqrt(np.mean(x * x, axis=-1, keepdims=True))
+
+
+def _m_rmsnorm_sum_not_mean(x, eps=1e-6):
+    x = np.asarray(x, dtype=np.float64)
+    return x / np.sqrt(np.sum(x * x, axis=-1, keepdims=True) + eps)
+
+
+def _m_bf16_truncate(a):
+    f = np.asarray(a, dtype=np.float64).astype(np.float32)
+    return (f.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+
+
+def _m_stack_residual_is_normalised(X0, layers, k, S=0, storage="bf16"):
+    x = O.widen(X0)
+    trace = []
+    for L in layers:
+        inp = O.round_to_bf16_bits(O.rmsnorm(x))
+        r = O.moe_layer(inp, L["Wr"], L["b"], L["Wg"], L["Wu"], L["Wd"], k, S)
+        r["inp"] = inp
+        trace.append(r)
+        x = O.widen(inp) + r["out"]
+    return x, trace
+
+
+def _m_stack_no_residual(X0, layers, k, S=0, storage="bf16"):
+    x = O.widen(X0)
+    trace = []
+    for L in layers:
+        inp = O.round_to_bf16_bits(O.rmsnorm(x))
+        r = O.moe_layer(inp, L["Wr"], L["b"], L["Wg"], L["Wu"], L["Wd"], k, S)
+        r["inp"] = inp
+        trace.append(r)
+        x = r["out"]
+    return x, trace
+
+
 MUTATIONS = [
+    ("routing_margins", _m_margins_topk_only, [check_routing_margins_hand_worked]),
+    ("routing_margins", _m_margins_all_gaps, [check_routing_margins_hand_worked]),
+    ("routing_margins", _m_margins_boundary_only, [check_routing_margins_hand_worked]),
+    ("rmsnorm", _m_rmsnorm_sum_not_mean, [check_rmsnorm_and_stack, check_stack_bf16_hand_worked]),
+    ("rmsnorm", _m_rmsnorm_no_eps, [check_rmsnorm_and_stack]),
+    ("round_to_bf16_bits", _m_bf16_truncate, [check_bf16_rounding, check_stack_bf16_hand_worked]),
+    ("moe_stack", _m_stack_residual_is_normalised, [check_stack_bf16_hand_worked]),
+    ("moe_stack", _m_stack_no_residual, [check_stack_bf16_hand_worked]),
     ("gate_weights", _m_no_renorm, [check_softmax_closed_form, check_weights_sum_and_order]),
     ("gate_weights", _m_softmax_selected_only_wrong, [check_softmax_closed_form]),
     ("silu", _m_silu_sign, [check_ffn_closed_form, check_ffn_vs_pure_python]),
