@@ -9,11 +9,18 @@ rotate over several distinct weight sets so that no step finds its weights in
 the 256 MB last-level cache.
 
 Prints ONE JSON line.  `value` = tokens/s of the whole layer with inputs
-already in HBM.  `roofline` prices the dominant kernel (gate/up weight stream)
-against the 8 TB/s HBM peak using its algorithmic bytes and its average
-duration measured with HIP events recorded between the kernels inside the
-timed region.  `cpu_baseline` times the fp64 CPU oracle on a bounded sample of
-the same batch on this machine's host cores.
+already in HBM (mean over the K timed steps; `ms_per_step_median` comes from
+a second, untimed pass with one event pair per step).  `roofline` prices the
+dominant kernel (gate/up weight stream) against the 8 TB/s HBM peak using its
+algorithmic bytes and its average duration measured with HIP events recorded
+between the kernels inside the timed region; `roofline.layer` prices the whole
+layer step the same way; `roofline.traffic` is read from the committed counter
+summaries under profiles/ and is null unless one was measured on this very
+kernel, workload and library version.  `cpu_baseline` times the fp64 CPU
+oracle on a bounded sample of the same batch on this machine's host cores, and
+`parity_err` compares the timed configuration's output with those oracle rows.
+`other_workloads` appends short runs of the Mixtral batch sweep (1, 8, 256
+tokens) and of the fine-grained, prefill and Qwen3-shaped layers.
 """
 from __future__ import annotations
 
@@ -29,11 +36,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-
-# HBM bytes per launch of the dominant kernel from hardware counters (FETCH_SIZE and
-# WRITE_SIZE, scaled by what the same counters read for a plain copy of known size);
-# measured offline, see profiles/gate_up_c2_mixtral_b64_hbm_traffic.md.
-MEASURED_TRAFFIC_BYTES = {("c2_mixtral", 64, "tiled"): 1884036096}
+MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
 def parse():
@@ -67,6 +70,9 @@ def parse():
     ap.add_argument("--layout", default="tiled", choices=["tiled", "row_major"],
                     help="expert weight layout in HBM (tiled = packed once at load time)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short runs of the batch sweep and the other layer shapes")
+    ap.add_argument("--other-steps", type=int, default=20)
     ap.add_argument("--probe", action="store_true",
                     help="also time a plain 1 GiB copy and a 4 GiB read (achievable HBM rate)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="0 = auto")
@@ -90,11 +96,13 @@ def cpu_baseline(cfg, L, X, n_tokens):
         n_tokens = int(max(2, min(X.shape[0], 20.0 / max(per_tok, 1e-6))))
     sample = list(range(min(n_tokens, X.shape[0])))
     t0 = time.perf_counter()
-    O.moe_layer(X, L["Wr"], L["b"], L["Wg"], L["Wu"], L["Wd"], cfg.k, cfg.S, tokens=sample)
+    ref = O.moe_layer(X, L["Wr"], L["b"], L["Wg"], L["Wu"], L["Wd"], cfg.k, cfg.S, tokens=sample)
     dt = time.perf_counter() - t0
-    return {"value": len(sample) / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+    return {"value": len(sample) / dt, "unit": "tokens/s", "cores": cores, "cpu_model": cpu_model(),
+            "kind": "oracle",
             "sample": f"{len(sample)} of the batch's {X.shape[0]} tokens through the fp64 oracle "
-                      f"(routing for all tokens, experts for the sample), {dt:.1f} s wall"}
+                      f"(routing for all tokens, experts for the sample), {dt:.1f} s wall",
+            "_ref": ref, "_sample": sample}
 
 
 def hbm_probe(torch, B):
@@ -297,26 +305,41 @@ def run_c5(args, torch, B):
     print(json.dumps(res_json))
 
 
-def main():
-    args = parse()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures one GPU only (the hot path is a single-GPU "
-              "kernel path; sharding by expert is a design note only). Run with --gpus 1.",
-              file=sys.stderr)
-        sys.exit(2)
+def traffic_from_profiles(kernel, workload, T, layout, lib):
+    """HBM bytes per launch of `kernel` from the committed counter summaries
+    (profiles/*.md): lines of the form
+        traffic_bytes: kernel=<name> workload=<w> tokens=<T> layout=<l> lib=<version> total=<bytes>
+    (no blanks inside a value: blanks of the version string are written as underscores)
+    written next to the rocprofv3 --pmc tables they summarise.  A figure is only
+    reported for the very kernel, workload and library version it was measured
+    on; anything else (a changed kernel bumps the version) gives None."""
+    import glob
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
+        for line in open(path):
+            if not line.startswith("traffic_bytes:"):
+                continue
+            kv = dict(tok.split("=", 1) for tok in line.split()[1:] if "=" in tok)
+            if (kv.get("kernel") == kernel and kv.get("workload") == workload
+                    and kv.get("tokens") == str(T) and kv.get("layout") == layout
+                    and kv.get("lib", "").replace("_", " ") == lib):
+                return {"bytes": int(kv["total"]), "source": os.path.relpath(path, ROOT)}
+    return None
 
-    import torch
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(3)
-    import paper_2509_23638_amd.binding as B
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def run_layer(args, torch, B, workload, T, steps, warmup, weight_sets, headline):
+    """One single-layer workload: K timed steps of the whole hot path."""
     from workloads import get_config, make_layer, make_hidden
-
-    if args.workload == "c5_stack":
-        return run_c5(args, torch, B)
-    cfg = get_config(args.workload)
-    T = args.tokens if args.workload == "c2_mixtral" else cfg.T
-    cfg = cfg.with_(T=T)
+    cfg = get_config(workload).with_(T=T)
     sh = B.make_shape(T, cfg.H, cfg.E, cfg.k, cfg.F, cfg.S, cfg.dtype, args.layout)
 
     def dev(a):
@@ -324,11 +347,11 @@ def main():
             else torch.from_numpy(a)
         return t.cuda()
 
-    layers, hosts = [], []
-    for i in range(args.weight_sets):
+    layers, host0 = [], None
+    for i in range(weight_sets):
         L = make_layer(cfg, layer=i, with_hidden=False, threads=16)
-        if i == 0:
-            hosts.append(L)
+        if i == 0 and headline:
+            host0 = L
         Wg, Wu, Wd = dev(L["Wg"]), dev(L["Wu"]), dev(L["Wd"])
         if args.layout == "tiled":   # the one-time load-time re-layout, outside the timed region
             Wg, Wu, Wd = B.pack_experts(Wg), B.pack_experts(Wu), B.pack_experts(Wd)
@@ -349,7 +372,7 @@ def main():
         n_active.append(int((views["count"] > 0).sum().item()))
 
     es = cfg.itemsize
-    A, rows = cfg.A, cfg.rows
+    rows = cfg.rows
 
     def gate_up_bytes(na):
         return (na + cfg.S) * 2 * cfg.F * cfg.H * es + T * cfg.H * es + rows * cfg.F * es
@@ -361,7 +384,7 @@ def main():
                 + 2 * rows * cfg.F * es                     # h written, read
                 + 2 * rows * cfg.H * 4)                     # Y written, read (fp32)
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         B.moe_layer_forward(ctx, sh, layers[i % len(layers)], X, out, ws)
     torch.cuda.synchronize()
 
@@ -371,54 +394,145 @@ def main():
     ctx.phase_times(reset=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         B.moe_layer_forward(ctx, sh, layers[i % len(layers)], X, out, ws)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ph2 = ctx.phase_times(reset=True)
-    # informational, outside the timed region: all five phases (six markers per step)
+    ctx.phase_timing(0)
+    # informational passes outside the timed region: one event pair per step (median
+    # step time), then all five phases (six markers per step)
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+             for _ in range(steps)]
+    for i, (e0, e1) in enumerate(pairs):
+        e0.record()
+        B.moe_layer_forward(ctx, sh, layers[i % len(layers)], X, out, ws)
+        e1.record()
+    torch.cuda.synchronize()
+    per_step = sorted(e0.elapsed_time(e1) for e0, e1 in pairs)
     ctx.phase_timing(1)
-    for i in range(args.steps):
+    for i in range(steps):
         B.moe_layer_forward(ctx, sh, layers[i % len(layers)], X, out, ws)
     torch.cuda.synchronize()
     ph = ctx.phase_times(reset=True)
     ctx.phase_timing(0)
 
-    ms_per_step = dt / args.steps * 1e3
-    value = T / (ms_per_step / 1e3)
-    used = [n_active[i % len(layers)] for i in range(args.steps)]
+    ms_per_step = dt / steps * 1e3
+    used = [n_active[i % len(layers)] for i in range(steps)]
     gu_bytes = float(np.mean([gate_up_bytes(n) for n in used]))
     all_bytes = float(np.mean([layer_bytes(n) for n in used]))
+    flops = 6.0 * rows * cfg.H * cfg.F
     gu_ms = ph2["gate_up_only_ms"] / max(1, ph2["gate_up_only_layers"])
     achieved = gu_bytes / (gu_ms * 1e-3) / 1e9 if gu_ms > 0 else 0.0
+    kernel = B.moe_ffn_kernel_name(sh, 0, cfg.E + cfg.S)
+    tr = traffic_from_profiles(kernel, workload, T, args.layout, B.moe_version())
+    res = {
+        "workload": workload, "tokens": T, "ms_per_step": ms_per_step,
+        "ms_per_step_median": per_step[len(per_step) // 2],
+        "tokens_per_s": T / (ms_per_step / 1e3), "active_experts": float(np.mean(used)),
+        "kernels": {"gate_up": kernel, "down": B.moe_ffn_kernel_name(sh, 1, cfg.E + cfg.S)},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": tr["bytes"] if tr else None,
+                     "traffic_source": tr["source"] if tr else None,
+                     "kernel": kernel, "kernel_ms": gu_ms, "algorithmic_bytes": gu_bytes,
+                     "layer": {"algorithmic_bytes": all_bytes,
+                               "achieved": all_bytes / (ms_per_step * 1e-3) / 1e9,
+                               "frac": all_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                               "flops": flops,
+                               "mfma_frac": flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}},
+        "phases_ms": {k: ph[k] / max(1, ph["n_layers"]) for k in
+                      ("route_ms", "permute_ms", "gate_up_ms", "down_ms", "combine_ms")},
+    }
+    if headline:
+        res["_cfg"], res["_host0"], res["_Xh"] = cfg, host0, Xh
+        # the timed configuration's own output on weight set 0, for the parity figure
+        B.moe_layer_forward(ctx, sh, layers[0], X, out, ws)
+        torch.cuda.synchronize()
+        res["_out"] = out.cpu()
+        res["_topk_idx"] = views["topk_idx"].cpu().numpy().copy()
+        if args.probe:
+            res["hbm_probe"] = hbm_probe(torch, B)
+    ctx.close()
+    del layers, ws, X, out
+    torch.cuda.empty_cache()
+    return res
 
+
+def parity_of_timed_output(res, base):
+    """Row-normalised error of the timed configuration's output against the
+    oracle rows the cpu_baseline leg computed (same weights, same tokens)."""
+    import torch
+    import oracle.moe_oracle as O
+    ref, sample = base.pop("_ref"), base.pop("_sample")
+    got = res["_out"]
+    got = O.widen(got.view(torch.int16).numpy().view(np.uint16)) if got.dtype == torch.bfloat16 \
+        else got.numpy().astype(np.float64)
+    num = np.abs(got[sample] - ref["out"][sample]).max(axis=1)
+    den = np.abs(ref["out"][sample]).max(axis=1)
+    return {"max_row_rel_err": float((num / den).max()), "tol": 2e-2 if res["_cfg"].dtype == "bf16" else 1e-5,
+            "routing_exact": bool(np.array_equal(res["_topk_idx"], ref["topk_idx"])),
+            "tokens_compared": len(sample)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (the hot path is a single-GPU "
+              "kernel path; sharding by expert is a design note only). Run with --gpus 1.",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    import paper_2509_23638_amd.binding as B
+    from workloads import get_config
+
+    if args.workload == "c5_stack":
+        return run_c5(args, torch, B)
+    T = args.tokens if args.workload == "c2_mixtral" else get_config(args.workload).T
+    r = run_layer(args, torch, B, args.workload, T, args.steps, args.warmup, args.weight_sets, True)
+    cfg = r["_cfg"]
     res = {
         "metric": "MoE-layer decode tokens/sec, Mixtral shape batch 64"
                   if args.workload == "c2_mixtral" else f"MoE-layer tokens/sec, {args.workload}",
-        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "value": r["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": r["ms_per_step"],
+        "ms_per_step_median": r["ms_per_step_median"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.dtype == "bf16" else "f32",
         "data": "synthetic",
         "config": {"workload": f"{args.workload} single MoE layer, T={T} decode tokens, "
                                f"H={cfg.H} E={cfg.E} top-{cfg.k} F={cfg.F} S={cfg.S}, all experts "
-                               f"resident ({args.layout} weight layout), {len(layers)} weight sets rotated",
-                   "tokens": T, "active_experts": float(np.mean(used))},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, T, args.layout)),
-                     "kernel": B.moe_ffn_kernel_name(sh, 0, cfg.E + cfg.S), "kernel_ms": gu_ms,
-                     "algorithmic_bytes": gu_bytes},
-        "phases_ms": {k: ph[k] / max(1, ph["n_layers"]) for k in
-                      ("route_ms", "permute_ms", "gate_up_ms", "down_ms", "combine_ms")},
-        "layer_hbm": {"algorithmic_bytes": all_bytes,
-                      "achieved_GBps": all_bytes / (ms_per_step * 1e-3) / 1e9,
-                      "frac_of_peak": all_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                               f"resident ({args.layout} weight layout), {args.weight_sets} weight sets rotated",
+                   "tokens": T, "active_experts": r["active_experts"], "library": B.moe_version()},
+        "roofline": r["roofline"], "phases_ms": r["phases_ms"], "kernels": r["kernels"],
     }
-    if args.probe:
-        res["hbm_probe"] = hbm_probe(torch, B)
+    if "hbm_probe" in r:
+        res["hbm_probe"] = r["hbm_probe"]
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(cfg, hosts[0], Xh, args.cpu_sample_tokens)
-    ctx.close()
+        base = cpu_baseline(cfg, r["_host0"], r["_Xh"], args.cpu_sample_tokens)
+        res["parity_err"] = parity_of_timed_output(r, base)
+        res["cpu_baseline"] = base
+    for k_ in [k_ for k_ in r if k_.startswith("_")]:
+        del r[k_]
+    # the other single-layer workloads, a few steps each (same harness, untouched kernels):
+    # the Mixtral batch sweep, the fine-grained, prefill and Qwen3-shaped layers
+    if not args.no_other_workloads and args.workload == "c2_mixtral" and T == 64:
+        others = []
+        plan = [("c2_mixtral", t, args.weight_sets) for t in (1, 8, 256)] + \
+               [(w, get_config(w).T, 2) for w in ("c3_finegrained", "c4_dsv2lite_prefill", "c6_qwen3_a3b")]
+        for w, t, sets in plan:
+            o = run_layer(args, torch, B, w, t, args.other_steps, 5, sets, False)
+            others.append({"workload": w, "tokens": t, "ms_per_step": o["ms_per_step"],
+                           "ms_per_step_median": o["ms_per_step_median"],
+                           "tokens_per_s": o["tokens_per_s"], "active_experts": o["active_experts"],
+                           "layer_hbm_frac": o["roofline"]["layer"]["frac"],
+                           "layer_mfma_frac": o["roofline"]["layer"]["mfma_frac"],
+                           "gate_up_hbm_frac": o["roofline"]["frac"], "kernels": o["kernels"],
+                           "phases_ms": o["phases_ms"]})
+        res["other_workloads"] = others
     print(json.dumps(res))
 
 

@@ -132,7 +132,9 @@ moe_status moe_route(const moe_shape* shape, const void* X, const void* Wr,
  *   perm [A] (perm[p] = assignment at bucket position p),
  *   inv_perm [A] (inv_perm[i] = bucket position of assignment i)  -- outputs
  * An index outside [0,E) is not detected at enqueue time; such an assignment
- * is dropped from every bucket and its inv_perm entry is set to -1. */
+ * is dropped from every bucket and its inv_perm entry is set to -1.
+ * Precondition for what consumes the buckets: the k indices of a token are
+ * distinct (moe_route guarantees it), so that no bucket holds more than T rows. */
 moe_status moe_permute(const moe_shape* shape, const int32_t* topk_idx,
                        int32_t* count, int32_t* offset, int32_t* perm,
                        int32_t* inv_perm, void* stream);
@@ -151,6 +153,10 @@ moe_status moe_pack_weights(const void* src, void* dst, int32_t N, int32_t K, vo
  *     Y[A + s*T + t, :] = FFN_{E+s}(x_t).
  * Experts with an empty bucket or a cleared bit read no weight bytes and leave
  * their rows of Y untouched.
+ * Precondition: no bucket holds more than T rows (true whenever a token's k
+ * experts are distinct, as moe_route produces them).  The kernels size their
+ * grids by T; rows of a bucket beyond its first T are not computed and their
+ * rows of Y stay untouched.  This cannot be checked at enqueue time.
  *   X [T,H] storage dtype; perm [A], offset [E+1] as produced by moe_permute
  *   host_experts: HOST array [E+S] of device pointers (copied at enqueue time;
  *                 entries of experts excluded by the mask may be NULL)
@@ -310,8 +316,10 @@ moe_status moe_probe_read(const void* src, size_t bytes, void* sink4, void* stre
 moe_status moe_probe_read_nt(const void* src, size_t bytes, void* sink4, void* stream);
 
 /* Which kernel the grouped FFN launches for a shape (measurement aid for
- * reports): phase 0 = gate/up, 1 = down; n_groups = experts listed in the call
- * (routed + shared).  Returns a static string, "" for an invalid request. */
+ * reports): phase 0 = gate/up, 1 = down.  The choice depends on the shape
+ * alone; n_groups (experts listed in a call) is accepted and ignored, so a
+ * call over a subset of experts runs the same kernels, bit for bit, as a call
+ * over all of them.  Returns a static string, "" for an invalid request. */
 const char* moe_ffn_kernel_name(const moe_shape* shape, int32_t phase, int32_t n_groups);
 
 /* Views into a workspace after moe_layer_forward (device pointers into

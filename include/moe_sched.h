@@ -53,6 +53,32 @@ moe_status moe_predict_counts(const moe_shape* shape, const void* X, const void*
                               const float* bias_next, int32_t* pred_count, void* workspace,
                               void* stream);
 
+/* The pending experts of a layer for a scheduling decision (Premise 1 of
+ * Section 4.3.2: experts that are activated, or predicted, and are neither on
+ * the GPU nor being loaded): every e < E with host_count[e] > 0 whose bit is
+ * clear in host_resident_mask and in host_in_flight_mask.  Host only.
+ *   host_count [E] tokens per expert (activated or predicted)
+ *   host_resident_mask, host_in_flight_mask: ceil(E/64) words, bit e of word
+ *     e/64; either may be NULL (= no expert resident / none in flight)
+ *   host_pending [E] receives the entries by ascending expert id,
+ *   *n_pending their number.
+ * Errors: NULL count / output, E outside [1, 128], a negative count. */
+typedef struct { int32_t expert; int32_t tokens; } moe_pending;
+moe_status moe_pending_experts(const int32_t* host_count, int32_t E,
+                               const uint64_t* host_resident_mask,
+                               const uint64_t* host_in_flight_mask,
+                               moe_pending* host_pending, int32_t* n_pending);
+
+/* Fixed-count prefetch policy (the one Section 5.3's ablation falls back to
+ * without PreSched: a fixed number of experts per layer): the n_prefetch
+ * pending experts with the most tokens, equal counts by ascending expert id,
+ * hottest first.  Host only.
+ *   host_chosen [min(n_prefetch, n_pending)] expert ids in issue order,
+ *   *n_chosen their number.  n_prefetch <= 0 chooses none.
+ * Errors: NULL pointer with a positive length, n_pending outside [0, 128]. */
+moe_status moe_prefetch_hottest(const moe_pending* host_pending, int32_t n_pending,
+                                int32_t n_prefetch, int32_t* host_chosen, int32_t* n_chosen);
+
 /* Cost inputs of PreSched (Section 4.3.2, "Constraints"); any time unit, used
  * consistently.  t_c(m) = beta*m + C is Eq. 2. */
 typedef struct {
@@ -68,9 +94,8 @@ typedef struct {
                               loaded, the queue holds all of E_all and i' = 0 */
 } moe_presched_costs;
 
-/* One expert that is activated (current layer) or predicted (next layer) and is
- * neither on the GPU nor being loaded (Premise 1). */
-typedef struct { int32_t expert; int32_t tokens; } moe_pending;
+/* moe_pending (above): one expert that is activated (current layer) or predicted
+ * (next layer) and is neither on the GPU nor being loaded (Premise 1). */
 
 typedef struct {
   int32_t n_cur, n_next;                      /* n + 1 and n' of the paper              */

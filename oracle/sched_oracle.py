@@ -29,7 +29,9 @@ Readings taken where the paper is silent or at odds with itself:
     is then an empty sum, so T_gap = -alpha - (n+1) t_io and only t_attn (the
     time per layer in which the link has no on-demand work) opens a window.
 
-Pins (tests/test_sched_pins.py): two timelines worked by hand, the min-max
+Pins (tests/test_sched_pins.py): pending lists and the fixed-count policy by hand
+and against the block oracle's separately written prefetch-set routine; two
+timelines worked by hand, the min-max
 property of the recheck against a brute-force search, suffix/monotonicity
 invariants, degenerate cost models with known answers, brute-force ranking for
 the hot table, and the predictor against the block oracle's own routing.
@@ -70,6 +72,35 @@ def gate_based_counts(X_cur, Wr_next, b_next, k: int) -> np.ndarray:
     idx, _, _ = _block.route(X_cur, Wr_next, b_next, k)
     E = np.asarray(Wr_next).shape[0]
     return np.bincount(idx.reshape(-1), minlength=E).astype(np.int64)
+
+
+# ------------------------------------------- pending experts, fixed-count policy
+def pending_experts(counts: Sequence[int], resident: Sequence[bool],
+                    in_flight: Sequence[bool] = None) -> List[Tuple[int, int]]:
+    """Premise 1 of Section 4.3.2: the experts a scheduling decision ranges
+    over are those that are activated (or predicted) and neither on the GPU
+    nor being loaded.  Returns (expert, tokens) by ascending expert id."""
+    out = []
+    for e, m in enumerate(counts):
+        if m > 0 and not resident[e] and not (in_flight is not None and in_flight[e]):
+            out.append((e, int(m)))
+    return out
+
+
+def prefetch_hottest(pending: Sequence[Tuple[int, int]], n_prefetch: int) -> List[int]:
+    """The fixed-count policy Section 5.3's ablation uses in place of PreSched:
+    take the n_prefetch pending experts with the most tokens, hottest first.
+    Reading: equal counts go to the lower expert id."""
+    chosen = []
+    left = list(pending)
+    while left and len(chosen) < n_prefetch:
+        best = left[0]
+        for cand in left[1:]:
+            if cand[1] > best[1] or (cand[1] == best[1] and cand[0] < best[0]):
+                best = cand
+        chosen.append(best[0])
+        left.remove(best)
+    return chosen
 
 
 # ------------------------------------------------------------------ PreSched

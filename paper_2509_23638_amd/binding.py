@@ -127,9 +127,14 @@ _lib.moe_workspace_views.argtypes = [_SH, _P] + [C.POINTER(_P)] * 7
 _lib.moe_counter_add.argtypes = [_SH, _P, _P, _P]
 _lib.moe_hot_table.argtypes = [_P, C.c_int32, C.c_int32, C.c_int64, _P]
 _lib.moe_predict_counts.argtypes = [_SH, _P, _P, _P, _P, _P, _P]
+_lib.moe_pending_experts.argtypes = [_P, C.c_int32, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64),
+                                     C.POINTER(moe_pending), C.POINTER(C.c_int32)]
+_lib.moe_prefetch_hottest.argtypes = [C.POINTER(moe_pending), C.c_int32, C.c_int32,
+                                      C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
 _lib.moe_presched.argtypes = [C.POINTER(moe_presched_costs), C.POINTER(moe_pending), C.c_int32,
                               C.POINTER(moe_pending), C.c_int32, C.POINTER(moe_presched_plan)]
 for _n in ("moe_counter_add", "moe_hot_table", "moe_predict_counts", "moe_presched",
+           "moe_pending_experts", "moe_prefetch_hottest",
            "moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_create",
            "moe_destroy", "moe_layer_forward", "moe_stream_totals_get", "moe_workspace_views",
            "moe_phase_timing", "moe_phase_times_get", "moe_probe_copy", "moe_probe_read",
@@ -142,7 +147,7 @@ EXPORTS = ["moe_version", "moe_last_error", "moe_workspace_bytes", "moe_route", 
            "moe_phase_times_get", "moe_probe_copy", "moe_probe_read", "moe_probe_read_nt",
            "moe_rmsnorm", "moe_set_option", "moe_pack_weights",
            "moe_counter_add", "moe_hot_table", "moe_predict_counts", "moe_presched",
-           "moe_ffn_kernel_name"]
+           "moe_ffn_kernel_name", "moe_pending_experts", "moe_prefetch_hottest"]
 
 
 def _check(st: int):
@@ -463,6 +468,29 @@ def moe_predict_counts(shape, X, Wr_next, bias_next, pred_count, workspace, stre
         _ptr(bias_next, "bias_next", (torch.float32,), shape.E),
         _ptr(pred_count, "pred_count", (torch.int32,), shape.E),
         _ptr(workspace, "workspace"), _stream(stream)))
+
+
+def moe_pending_experts(counts, resident=None, in_flight=None):
+    """counts: E ints on the host; resident / in_flight: bool sequences or None.
+    Returns [(expert, tokens)] by ascending expert id."""
+    E = len(counts)
+    arr = (C.c_int32 * E)(*[int(c) for c in counts])
+    out = (moe_pending * E)()
+    n = C.c_int32(0)
+    _check(_lib.moe_pending_experts(arr, E, _mask_words(resident, E), _mask_words(in_flight, E),
+                                    out, C.byref(n)))
+    return [(out[i].expert, out[i].tokens) for i in range(n.value)]
+
+
+def moe_prefetch_hottest(pending, n_prefetch: int):
+    """pending: [(expert, tokens)] -> expert ids in issue order."""
+    arr = (moe_pending * max(1, len(pending)))()
+    for i, (e, m) in enumerate(pending):
+        arr[i].expert, arr[i].tokens = int(e), int(m)
+    out = (C.c_int32 * max(1, len(pending)))()
+    n = C.c_int32(0)
+    _check(_lib.moe_prefetch_hottest(arr, len(pending), int(n_prefetch), out, C.byref(n)))
+    return [out[i] for i in range(n.value)]
 
 
 def moe_presched(costs: moe_presched_costs, cur, nxt) -> moe_presched_plan:

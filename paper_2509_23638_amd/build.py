@@ -37,11 +37,13 @@ def build(verbose: bool = True) -> str:
     from concurrent.futures import ThreadPoolExecutor
 
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    # measurement builds only: compile the MOE_TUNE_* kernel-selection overrides in
+    flags = FLAGS + (["-DMOE_TUNING"] if os.environ.get("MOE_BUILD_TUNING") == "1" else [])
     os.makedirs(OBJDIR, exist_ok=True)
     objs = [os.path.join(OBJDIR, s.replace(".hip", ".o")) for s in SOURCES]
     jobs = min(len(SOURCES), int(os.environ.get("MAX_JOBS", "8")), os.cpu_count() or 1)
     with ThreadPoolExecutor(max_workers=max(jobs, 1)) as pool:
-        list(pool.map(lambda so: _run([hipcc, *FLAGS, "-c", os.path.join(CSRC, so[0]), "-o", so[1]],
+        list(pool.map(lambda so: _run([hipcc, *flags, "-c", os.path.join(CSRC, so[0]), "-o", so[1]],
                                       verbose), zip(SOURCES, objs)))
     _run([hipcc, "--offload-arch=gfx950", "-fPIC", "-shared", *objs, "-o", LIB], verbose)
     return LIB

@@ -36,6 +36,16 @@ moe_status check_shape(const moe_shape* s, const char* who);
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Kernel-selection overrides for measurement sweeps (environment variables
+// MOE_TUNE_*).  They exist only in a library compiled with -DMOE_TUNING
+// (build.py: MOE_BUILD_TUNING=1); the product build ignores the environment,
+// so a stray variable can never change which kernels run or the order of a sum.
+#ifdef MOE_TUNING
+const char* tune_env(const char* name);
+#else
+static inline const char* tune_env(const char*) { return nullptr; }
+#endif
+
 // Workspace carve-up (all offsets 256-byte aligned).
 struct WorkspaceLayout {
   size_t topk_idx, topk_w, count, offset, perm, inv_perm, logits, h, y, total;

@@ -1,6 +1,7 @@
 // Shape validation, error strings, workspace carve-up.
 #include "common.h"
 
+#include <stdlib.h>
 #include <string.h>
 
 namespace moe {
@@ -14,6 +15,10 @@ moe_status fail(moe_status st, const char* fmt, ...) {
   va_end(ap);
   return st;
 }
+
+#ifdef MOE_TUNING
+const char* tune_env(const char* name) { return getenv(name); }
+#endif
 
 moe_status check_shape(const moe_shape* s, const char* who) {
   if (!s) return fail(MOE_ERR_INVALID_ARG, "%s: NULL shape", who);
@@ -58,7 +63,13 @@ WorkspaceLayout workspace_layout(const moe_shape& s) {
 
 }  // namespace moe
 
-extern "C" const char* moe_version(void) { return "moe_hotpath 0.1 (gfx950)"; }
+extern "C" const char* moe_version(void) {
+#ifdef MOE_TUNING
+  return "moe_hotpath 0.2 (gfx950, tuning build: MOE_TUNE_* overrides compiled in)";
+#else
+  return "moe_hotpath 0.2 (gfx950)";
+#endif
+}
 
 extern "C" const char* moe_last_error(void) { return moe::g_err; }
 

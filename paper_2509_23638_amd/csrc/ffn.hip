@@ -28,6 +28,7 @@
 #include <stdlib.h>
 
 #include <algorithm>
+#include <mutex>
 #include <type_traits>
 
 namespace moe {
@@ -809,6 +810,7 @@ __global__ __launch_bounds__(kThreads, 1) void ffn_tile_kernel(FfnArgs a, Expert
 
 // ----------------------------------- tiled kernel, at most 64 tokens ----
 constexpr int kSmallNJ = 2;   // token tiles per wave: blocks of at most 64 rows
+constexpr int kSmallRows = 32 * kSmallNJ;
 
 // Issue this wave's fetches of an item's stage st into ring buffer `slot`: the
 // first NTOK of its eight token fetches (token blocks 0 .. 2 NTOK - 1 of the
@@ -943,7 +945,7 @@ __device__ __forceinline__ void ffn_small_block(const FfnArgs& a, const ExpertTa
   // The stores go through a buffer resource that covers this block's rows of the
   // output and nothing else: a row past the bucket's end is out of its range and
   // the hardware drops the store, so every wave issues the same number of stores.
-  const int block_rows = __builtin_amdgcn_readfirstlane(min(row_end - r0, kTileRows));
+  const int block_rows = __builtin_amdgcn_readfirstlane(min(row_end - r0, kSmallRows));
   const size_t out_elt = MODE == kGateUp ? 2 : 4;
   const size_t block_base = (size_t)__builtin_amdgcn_readfirstlane(r0) * a.N * out_elt;
   const ActRsrc out_rsrc = __builtin_amdgcn_make_buffer_rsrc(
@@ -1086,7 +1088,9 @@ __global__ __launch_bounds__(kThreads, 1) void ffn_tile_small_kernel(FfnArgs a, 
                                                                      GroupList groups) {
   extern __shared__ __attribute__((aligned(16))) unsigned char ring[];
   __shared__ TilePlan plan;
-  tile_plan_build(plan, a, groups);
+  // blocks of at most 64 rows: a bucket that holds more (possible only when a
+  // caller's top-k lists name an expert twice for one token) is split, never cut
+  tile_plan_build<kSmallRows>(plan, a, groups);
   const int slabs = a.N / (MODE == kGateUp ? 64 : 128);
   const int total = plan.first[groups.n] * slabs;
   const int xcd = blockIdx.x & 7, stride = gridDim.x >> 3;   // grid is a multiple of 8
@@ -1096,7 +1100,7 @@ __global__ __launch_bounds__(kThreads, 1) void ffn_tile_small_kernel(FfnArgs a, 
   const int lane = threadIdx.x & (MOE_WAVE - 1), wave = threadIdx.x / MOE_WAVE;
   const int w_adv = a.tiled ? 1024 : kTileK;
 
-  TileItem it = tile_item(groups, plan, order.item(local), slabs);
+  TileItem it = tile_item<kSmallRows>(groups, plan, order.item(local), slabs);
   const uint16_t* src[kFetchPerWave];
   {
     int rows[8];
@@ -1110,7 +1114,7 @@ __global__ __launch_bounds__(kThreads, 1) void ffn_tile_small_kernel(FfnArgs a, 
   while (true) {
     const bool has_next = local + stride < order.count;
     TileItem nxt = it;
-    if (has_next) nxt = tile_item(groups, plan, order.item(local + stride), slabs);
+    if (has_next) nxt = tile_item<kSmallRows>(groups, plan, order.item(local + stride), slabs);
     ffn_small_block<MODE>(a, tab, it, has_next, nxt, src, ring, older_stores, slot0);
     older_stores = small_stores<MODE>();
     if (!has_next) break;
@@ -1472,9 +1476,9 @@ int max_row_blocks(const moe_shape& s, int block_rows) {
 // the token matrix is small enough to sit in every XCD's 4 MB L2 next to the
 // weight stream; the kernel then uses it if the buckets are uneven.  (For the
 // down projection, whose activations are the much larger h, it measured slower
-// at every size.)  MOE_TUNE_INTERLEAVE=0|1 overrides (measurement aid).
+// at every size.)  MOE_TUNE_INTERLEAVE=0|1 overrides (tuning builds only).
 int interleave_allowed(long long act_bytes) {
-  static const char* env = getenv("MOE_TUNE_INTERLEAVE");
+  static const char* env = tune_env("MOE_TUNE_INTERLEAVE");
   if (env && (env[0] == '0' || env[0] == '1')) return env[0] == '1';
   return act_bytes <= (4ll << 20);
 }
@@ -1483,43 +1487,71 @@ int interleave_allowed(long long act_bytes) {
 // well filled, if the output width is a multiple of its slab, the contraction
 // is long enough for its fixed pipeline and the activation matrix fits a
 // 32-bit buffer offset.  MOE_TUNE_WIDE=0|1 overrides the first
-// condition (measurement aid).
+// condition (tuning builds only).
 bool wide_form(const moe_shape& s, int phase) {
   const long long K = phase == 0 ? s.H : s.F;
   const long long act_rows = phase == 0 ? (long long)s.T : (long long)s.T * s.k + (long long)s.S * s.T;
   const int N = phase == 0 ? s.F : s.H;
   if (N % (phase == 0 ? kWideSlabGateUp : kWideSlabDown) != 0) return false;
   if (K / kTileK < kWideMinStages || act_rows * K * 2 >= (1ll << 31)) return false;
-  static const char* env = getenv("MOE_TUNE_WIDE");
+  static const char* env = tune_env("MOE_TUNE_WIDE");
   if (env && (env[0] == '0' || env[0] == '1')) return env[0] == '1';
   const double rows = (double)s.T * s.k / s.E;
   return rows >= 96.0 || (s.S > 0 && s.T > 256);
 }
 
+// Per-device launch state of the tiled kernels: the dynamic-LDS attribute has to
+// be set once per kernel and device, and the persistent grids are sized by the
+// device's compute units.
+constexpr int kMaxDevices = 64;
+struct TileDeviceState {
+  std::once_flag once[2];      // per phase (the kernels are templates over it)
+  hipError_t err[2] = {hipSuccess, hipSuccess};
+  int n_cu = 0;
+};
+TileDeviceState g_tile_state[kMaxDevices];
+
+template <int MODE>
+hipError_t tile_attributes() {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_tile_kernel<MODE>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, kTileLds);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_tile_small_kernel<MODE>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kTileLds);
+  if (e != hipSuccess) return e;
+  for (int r = 0; r < kWideWeightSets; ++r) {
+    e = hipFuncSetAttribute(WideKernels<MODE>::get(r), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            kWideLds);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
 template <int MODE>
 moe_status launch_tile(const moe_shape& s, const FfnArgs& args, const ExpertTable& tab,
                        const GroupList& groups, hipStream_t stream, bool wide) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    MOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_tile_kernel<MODE>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kTileLds));
-    MOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_tile_small_kernel<MODE>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kTileLds));
-    for (int r = 0; r < kWideWeightSets; ++r)
-      MOE_HIP(hipFuncSetAttribute(WideKernels<MODE>::get(r),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, kWideLds));
-    attr_set = true;
-  }
+  int dev = 0;
+  MOE_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(MOE_ERR_UNSUPPORTED, "device index %d out of range", dev);
+  TileDeviceState& ds = g_tile_state[dev];
+  constexpr int ph = MODE == kGateUp ? 0 : 1;
+  std::call_once(ds.once[ph], [&]() {
+    ds.err[ph] = tile_attributes<MODE>();
+    if (ds.err[ph] == hipSuccess && !ds.n_cu) {
+      int n = 0;
+      ds.err[ph] = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+      ds.n_cu = n;
+    }
+  });
+  if (ds.err[ph] != hipSuccess)
+    return fail(MOE_ERR_HIP, "tiled FFN kernel set-up: %s", hipGetErrorString(ds.err[ph]));
+  int n_cu = ds.n_cu;
+  if (!n_cu) MOE_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
   const int slabs = wide ? (MODE == kGateUp ? s.F / kWideSlabGateUp : s.H / kWideSlabDown)
                          : (MODE == kGateUp ? s.F / 64 : s.H / 128);
   // one persistent workgroup per compute unit, never more than there can be items
-  static int n_cu = 0;
-  if (!n_cu) {
-    int dev = 0;
-    MOE_HIP(hipGetDevice(&dev));
-    MOE_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
-  }
-  const int grid = (std::min(slabs * max_row_blocks(s, wide ? kWideRows : kTileRows), n_cu) + 7) / 8 * 8;
+  const int block_rows = wide ? kWideRows : (s.T <= kSmallRows ? kSmallRows : kTileRows);
+  const int grid = (std::min(slabs * max_row_blocks(s, block_rows), n_cu) + 7) / 8 * 8;
   if (wide) {
     // rows of the activation matrix: tokens for gate/up, bucket rows for down
     long long act_rows = MODE == kGateUp ? (long long)s.T : (long long)args.A + (long long)s.S * s.T;
@@ -1529,7 +1561,7 @@ moe_status launch_tile(const moe_shape& s, const FfnArgs& args, const ExpertTabl
     MOE_HIP(hipLaunchKernel(WideKernels<MODE>::get(r), dim3(grid), dim3(kWideThreads), params,
                             kWideLds, stream));
   } else {
-    if (s.T <= 64)   // every bucket, a shared expert's too, has at most T rows
+    if (s.T <= kSmallRows)   // every bucket, a shared expert's too, has at most T rows
       hipLaunchKernelGGL((ffn_tile_small_kernel<MODE>), dim3(grid), dim3(kThreads), kTileLds, stream,
                          args, tab, groups);
     else
@@ -1760,14 +1792,14 @@ __global__ __launch_bounds__(kThreads) void ffn_f32_kernel(F32Args a, ExpertTabl
 // about 24 rows per expert on.
 // MOE_TUNE_BLOCK=0|1|3 forces stream64 / stream128 / tile for both phases,
 // MOE_TUNE_GU=0|1|3 for gate/up only, MOE_TUNE_DOWN=lds|splitk|halves|tile
-// for down only (measurement aids).
+// for down only (tuning builds only, see tune_env).
 enum Variant { kStream64 = 0, kStream128 = 1, kTile = 3, kSplitK = 4, kHalves = 5 };
 
 // The tiled kernel walks the contraction in steps of 64 and owns 64 / 128 rows.
 bool tile_kernel_fits(const moe_shape& s) { return s.H % 128 == 0 && s.F % 64 == 0; }
 
 static int forced_block() {
-  static const char* env = getenv("MOE_TUNE_BLOCK");
+  static const char* env = tune_env("MOE_TUNE_BLOCK");
   return (env && (env[0] == '0' || env[0] == '1' || env[0] == '3')) ? env[0] - '0' : -1;
 }
 
@@ -1779,19 +1811,23 @@ static Variant rows_rule(const moe_shape& s) {
 }
 
 Variant gate_up_variant(const moe_shape& s, int n_groups) {
-  static const char* env = getenv("MOE_TUNE_GU");
+  static const char* env = tune_env("MOE_TUNE_GU");
   if (env && (env[0] == '0' || env[0] == '1' || env[0] == '3')) return (Variant)(env[0] - '0');
   if (forced_block() >= 0) return (Variant)forced_block();
   const Variant v = rows_rule(s);
   // wide experts: many slabs per expert, so the persistent workgroups get even
-  // shares whatever number of experts turns out to be active
-  if (v != kTile && tile_kernel_fits(s) && s.F / 64 >= 64 && (long)n_groups * (s.F / 64) >= 2 * 256)
+  // shares whatever number of experts turns out to be active.  Decided by the
+  // layer's shape, not by how many experts this call lists: the streamed path
+  // runs one expert per call and must land on the same kernel (same order of
+  // every sum, same bits) as the all-resident call.
+  (void)n_groups;
+  if (v != kTile && tile_kernel_fits(s) && s.F / 64 >= 64 && (long)(s.E + s.S) * (s.F / 64) >= 2 * 256)
     return kTile;
   return v;
 }
 
 Variant down_variant(const moe_shape& s) {
-  static const char* env = getenv("MOE_TUNE_DOWN");
+  static const char* env = tune_env("MOE_TUNE_DOWN");
   const bool halves_ok = (s.F / kChunk) % 2 == 0;
   if (env && env[0] == 'l') return kStream64;
   if (env && env[0] == 's') return kSplitK;

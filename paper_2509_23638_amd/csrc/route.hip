@@ -434,7 +434,7 @@ bool launch_logits(const moe_shape& s, const void* X, const void* Wr, const floa
     LOGITS_LAUNCH(8, 1, 1, 8, 1, false, true);
     return true;
   }
-  static const char* tune = getenv("MOE_TUNE_ROUTE_MFMA");   // measurement aid: tile threshold
+  static const char* tune = tune_env("MOE_TUNE_ROUTE_MFMA");   // measurement aid: tile threshold
   if (blocks(16, 16) >= (tune ? atol(tune) : kMfmaTiles)) {
     // many tokens: 16 x 16 tiles on the float64 matrix cores; enough waves
     // along the hidden dimension to give every SIMD two

@@ -96,6 +96,43 @@ extern "C" moe_status moe_predict_counts(const moe_shape* shape, const void* X, 
   return MOE_OK;
 }
 
+extern "C" moe_status moe_pending_experts(const int32_t* host_count, int32_t E,
+                                          const uint64_t* host_resident_mask,
+                                          const uint64_t* host_in_flight_mask,
+                                          moe_pending* host_pending, int32_t* n_pending) {
+  MOE_REQUIRE(host_count && host_pending && n_pending, "moe_pending_experts: NULL pointer argument");
+  MOE_REQUIRE(E >= 1 && E <= MOE_SCHED_MAX_EXPERTS, "moe_pending_experts: E=%d outside [1, %d]", E,
+              MOE_SCHED_MAX_EXPERTS);
+  int n = 0;
+  for (int e = 0; e < E; ++e) {
+    MOE_REQUIRE(host_count[e] >= 0, "moe_pending_experts: negative count for expert %d", e);
+    const bool resident = host_resident_mask && ((host_resident_mask[e >> 6] >> (e & 63)) & 1ull);
+    const bool in_flight = host_in_flight_mask && ((host_in_flight_mask[e >> 6] >> (e & 63)) & 1ull);
+    if (host_count[e] > 0 && !resident && !in_flight) host_pending[n++] = {e, host_count[e]};
+  }
+  *n_pending = n;
+  return MOE_OK;
+}
+
+extern "C" moe_status moe_prefetch_hottest(const moe_pending* host_pending, int32_t n_pending,
+                                           int32_t n_prefetch, int32_t* host_chosen,
+                                           int32_t* n_chosen) {
+  MOE_REQUIRE(n_chosen, "moe_prefetch_hottest: NULL n_chosen");
+  MOE_REQUIRE(n_pending >= 0 && n_pending <= MOE_SCHED_MAX_EXPERTS,
+              "moe_prefetch_hottest: n_pending=%d outside [0, %d]", n_pending, MOE_SCHED_MAX_EXPERTS);
+  *n_chosen = 0;
+  const int take = std::min(std::max(n_prefetch, 0), n_pending);
+  if (take == 0) return MOE_OK;
+  MOE_REQUIRE(host_pending && host_chosen, "moe_prefetch_hottest: NULL list with a positive length");
+  std::vector<moe_pending> order(host_pending, host_pending + n_pending);
+  std::sort(order.begin(), order.end(), [](const moe_pending& a, const moe_pending& b) {
+    return a.tokens != b.tokens ? a.tokens > b.tokens : a.expert < b.expert;
+  });
+  for (int i = 0; i < take; ++i) host_chosen[i] = order[i].expert;
+  *n_chosen = take;
+  return MOE_OK;
+}
+
 extern "C" moe_status moe_presched(const moe_presched_costs* c, const moe_pending* host_cur,
                                    int32_t n_cur, const moe_pending* host_next, int32_t n_next,
                                    moe_presched_plan* out) {

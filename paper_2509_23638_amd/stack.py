@@ -155,14 +155,13 @@ class StreamedStack:
             pm = None
             if nxt is not None and policy != "none":
                 pred = self.predicted_counts(nxt, self._norm, self._pred)
-                cand = [(e, int(pred[e])) for e in range(E)
-                        if pred[e] > 0 and not self.resident[nxt][e]]
+                cand = B.moe_pending_experts(pred, self.resident[nxt])
                 if policy == "gate_topn":
-                    chosen = [e for e, _ in sorted(cand, key=lambda r: (-r[1], r[0]))[:n_prefetch]]
+                    chosen = B.moe_prefetch_hottest(cand, n_prefetch)
                 elif policy == "presched":
                     mine = self.predicted_counts(l, self._norm, self._cur)
-                    cur = [(e, int(mine[e])) for e in range(E)
-                           if mine[e] > 0 and not self.resident[l][e] and e not in self._in_slot[l]]
+                    in_slot = [e in self._in_slot[l] for e in range(E)]
+                    cur = B.moe_pending_experts(mine, self.resident[l], in_slot)
                     plan = B.moe_presched(costs, cur, cand)
                     chosen = list(plan.prefetch[:min(plan.n_prefetch, n_prefetch)])
                     self.sched_log["n_decisions"] += 1

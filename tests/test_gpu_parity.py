@@ -277,6 +277,31 @@ def test_grouped_ffn_mask_leaves_rows_untouched(B):
             assert np.isnan(Yh[lo:hi]).all()
 
 
+def test_small_tiled_kernel_splits_an_overfull_bucket(B):
+    """The grouped FFN is public and takes any bucket list.  At most 64 tokens
+    select the small tiled kernel, which multiplies 64-row blocks: a bucket of
+    more than 64 rows (a caller's top-k list naming one expert twice per token)
+    must be split into blocks, not cut off after the first."""
+    cfg = _small("overfull", T=60, E=2, k=2, H=256, F=512, bias="none")
+    L = make_layer(cfg)
+    sh = _shape(B, cfg, layout="tiled")
+    assert "small" in B.moe_ffn_kernel_name(sh, 0, cfg.E) and "small" in B.moe_ffn_kernel_name(sh, 1, cfg.E)
+    A = cfg.A
+    idx = np.zeros((cfg.T, cfg.k), dtype=np.int32)          # every assignment goes to expert 0
+    count, offset, perm, inv = O.bucket_by_expert(idx, cfg.E)
+    assert count[0] == A == 120
+    Wg, Wu, Wd = _experts_dev(B, L, "tiled")
+    tab = B.expert_table(sh, Wg, Wu, Wd)
+    Y = torch.full((A, cfg.H), float("nan"), dtype=torch.float32, device="cuda")
+    ws = B.alloc_workspace(sh)
+    B.moe_grouped_ffn(sh, to_dev(L["X"]), to_dev(perm), to_dev(offset), tab, None, Y, ws)
+    torch.cuda.synchronize()
+    Yref = O.grouped_ffn_rows(L["X"], perm, offset, cfg.k, L["Wg"], L["Wu"], L["Wd"], 0)
+    Yh = Y.cpu().numpy()
+    assert np.isfinite(Yh).all()
+    assert row_rel_err(Yh, Yref) <= TOL["bf16"]
+
+
 def _layer_gpu(B, cfg, L, ctx=None, layout="row_major", dev_weights=None, want_rows=False, **kw):
     sh = _shape(B, cfg, L["X"].shape[0], layout=layout)
     own = ctx is None

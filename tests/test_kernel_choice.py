@@ -48,11 +48,29 @@ def test_choice_does_not_depend_on_the_number_of_listed_experts_once_blocks_are_
     """The streamed path calls the FFN over subsets of experts; with well-filled
     blocks every such call must land on the same kernels as the all-resident
     call (the eight-wave form is chosen from the shape alone)."""
-    cfg = get_config("c4_dsv2lite_prefill")
-    sh = B.make_shape(cfg.T, cfg.H, cfg.E, cfg.k, cfg.F, cfg.S, cfg.dtype, "tiled")
-    for phase in (0, 1):
-        names = {B.moe_ffn_kernel_name(sh, phase, n) for n in (1, 2, 7, 33, cfg.E + cfg.S)}
-        assert len(names) == 1, names
+    for name, T in (("c4_dsv2lite_prefill", None), ("c5_stack", None), ("c2_mixtral", 1),
+                    ("c2_mixtral", 64), ("c2_mixtral", 256), ("c3_finegrained", None),
+                    ("c6_qwen3_a3b", None)):
+        cfg = get_config(name)
+        sh = B.make_shape(T or cfg.T, cfg.H, cfg.E, cfg.k, cfg.F, cfg.S, cfg.dtype, "tiled")
+        for phase in (0, 1):
+            names = {B.moe_ffn_kernel_name(sh, phase, n) for n in (1, 2, 7, 33, cfg.E + cfg.S)}
+            assert len(names) == 1, (name, names)
+
+
+def test_the_small_tiled_kernel_is_chosen_by_the_token_count_alone(B):
+    """At most 64 tokens: every bucket of a well-formed routing fits one 64-row
+    block, which is what the small tiled kernel multiplies per item (it splits a
+    larger bucket into 64-row blocks rather than cutting it)."""
+    cfg = get_config("c2_mixtral")
+    for T, want in ((1, "small"), (64, "small"), (65, "tile_kernel"), (128, "tile_kernel")):
+        sh = B.make_shape(T, cfg.H, cfg.E, cfg.k, cfg.F, cfg.S, cfg.dtype, "tiled")
+        assert want in B.moe_ffn_kernel_name(sh, 0, cfg.E)
+
+
+def test_product_build_has_no_tuning_overrides(B):
+    """MOE_TUNE_* environment overrides exist only in measurement builds."""
+    assert "tuning" not in B.moe_version()
 
 
 def test_f32_storage_has_its_own_kernel(B):

@@ -84,3 +84,22 @@ def test_hot_table_matches_oracle(B):
             assert np.array_equal(B.moe_hot_table(tok, budget), S.hot_expert_table(tok, budget))
     with pytest.raises(B.MoEError):
         B.moe_hot_table(np.zeros((0, 4), dtype=np.int64), 1)
+
+
+def test_pending_list_and_fixed_count_policy_match_oracle(B):
+    r = np.random.Generator(np.random.PCG64(29))
+    for trial in range(400):
+        E = int(r.integers(1, 129)) if trial % 20 else 128
+        hi = 3 if trial % 2 else 500
+        counts = r.integers(0, hi, size=E).tolist()
+        res = (r.random(E) < 0.4).tolist()
+        fly = (r.random(E) < 0.2).tolist() if trial % 3 else None
+        pend = B.moe_pending_experts(counts, res, fly)
+        assert pend == S.pending_experts(counts, res, fly)
+        for n in (0, 1, 2, int(r.integers(0, E + 3))):
+            assert B.moe_prefetch_hottest(pend, n) == S.prefetch_hottest(pend, n)
+    assert B.moe_pending_experts([3, 0, 4], None, None) == [(0, 3), (2, 4)]
+    with pytest.raises(B.MoEError):
+        B.moe_pending_experts([1, -2], [False, False])
+    with pytest.raises(B.MoEError):
+        B.moe_prefetch_hottest([(i, 1) for i in range(129)], 2)

@@ -240,6 +240,48 @@ def check_gate_based_counts_by_inspection():
     assert S.gate_based_counts(X[:0], Wr, b, 2).tolist() == [0, 0, 0, 0]
 
 
+# -------------------------------------- pending list and fixed-count policy ---
+def check_pending_and_hottest_by_hand():
+    counts = [5, 0, 7, 7, 2, 9, 1, 7]
+    resident = [False, False, False, True, False, True, False, False]
+    in_flight = [False, False, False, False, True, False, False, False]
+    # expert 1 has no tokens, 3 and 5 are resident, 4 is being loaded
+    assert S.pending_experts(counts, resident) == [(0, 5), (2, 7), (4, 2), (6, 1), (7, 7)]
+    pend = S.pending_experts(counts, resident, in_flight)
+    assert pend == [(0, 5), (2, 7), (6, 1), (7, 7)]
+    # hottest first; 2 and 7 tie on 7 tokens: the lower id goes first
+    assert S.prefetch_hottest(pend, 1) == [2]
+    assert S.prefetch_hottest(pend, 2) == [2, 7]
+    assert S.prefetch_hottest(pend, 3) == [2, 7, 0]
+    assert S.prefetch_hottest(pend, 9) == [2, 7, 0, 6]
+    assert S.prefetch_hottest(pend, 0) == [] and S.prefetch_hottest([], 2) == []
+    # input order must not matter
+    assert S.prefetch_hottest(list(reversed(pend)), 3) == [2, 7, 0]
+
+
+def check_hottest_against_block_oracle_prefetch_set():
+    """oracle/moe_oracle.py states the same policy in its own words for the
+    benchmark's predictor stand-in (votes of the noisy top-k, best non-resident
+    experts with any vote, ties to the lower index); with zero noise the two
+    separately written routines must choose the same set."""
+    import oracle.moe_oracle as O
+    r = np.random.Generator(np.random.PCG64(50))
+    for trial in range(60):
+        E, T = int(r.integers(3, 24)), int(r.integers(1, 20))
+        k = int(r.integers(1, min(E, 5) + 1))
+        n = int(r.integers(0, 5))
+        lg = r.integers(-3, 4, size=(T, E)).astype(np.float64)      # many ties
+        res = r.random(E) < 0.4
+        want = O.predicted_prefetch_set(lg, np.zeros_like(lg), k, n, res)
+        votes = np.zeros(E, dtype=np.int64)
+        for t in range(T):
+            for e in O.select_topk(lg[t], k):
+                votes[e] += 1
+        got = np.zeros(E, dtype=bool)
+        got[S.prefetch_hottest(S.pending_experts(votes, res), n)] = True
+        assert np.array_equal(got, want)
+
+
 CHECKS = [v for k, v in sorted(globals().items()) if k.startswith("check_")]
 
 
@@ -298,6 +340,18 @@ MUTANTS = [
      [check_hot_table_by_hand_and_bruteforce]),
     ("hot_table_tie_order", ("key=lambda r: (-r[0], r[1], r[2])", "key=lambda r: (-r[0], -r[1], r[2])"),
      [check_hot_table_by_hand_and_bruteforce]),
+    ("pending_keeps_resident", ("if m > 0 and not resident[e] and not (", "if m > 0 and not ("),
+     [check_pending_and_hottest_by_hand, check_hottest_against_block_oracle_prefetch_set]),
+    ("pending_keeps_idle", ("if m > 0 and not resident[e]", "if m >= 0 and not resident[e]"),
+     [check_pending_and_hottest_by_hand, check_hottest_against_block_oracle_prefetch_set]),
+    ("pending_ignores_in_flight", ("and not (in_flight is not None and in_flight[e])", ""),
+     [check_pending_and_hottest_by_hand]),
+    ("hottest_takes_coldest", ("if cand[1] > best[1] or (cand[1] == best[1] and cand[0] < best[0]):",
+                               "if cand[1] < best[1] or (cand[1] == best[1] and cand[0] < best[0]):"),
+     [check_pending_and_hottest_by_hand, check_hottest_against_block_oracle_prefetch_set]),
+    ("hottest_tie_to_higher_id", ("(cand[1] == best[1] and cand[0] < best[0])",
+                                  "(cand[1] == best[1] and cand[0] > best[0])"),
+     [check_pending_and_hottest_by_hand, check_hottest_against_block_oracle_prefetch_set]),
     ("counts_own_layer_k", ("_block.route(X_cur, Wr_next, b_next, k)", "_block.route(X_cur, Wr_next, None, k)"),
      [check_gate_based_counts_by_inspection]),
 ]
@@ -307,7 +361,7 @@ MUTANTS = [
 def test_planted_mistake_is_caught(monkeypatch, name, edit, checks):
     """A mistake planted in the oracle (CPU only) must fail its pins."""
     mutant = _mutant_presched(edit)
-    for fn in ("presched", "hot_expert_table", "gate_based_counts"):
+    for fn in ("presched", "hot_expert_table", "gate_based_counts", "pending_experts", "prefetch_hottest"):
         monkeypatch.setattr(S, fn, getattr(mutant, fn))
     for check in checks:
         with pytest.raises(AssertionError):
