@@ -252,6 +252,28 @@ moe_status moe_layer_forward(moe_ctx* ctx, const moe_shape* shape,
                              void* workspace, void* stream,
                              moe_layer_stats* stats);
 
+/* ---- the block, for callers that cannot allocate ---------------------------
+ * For code under HIP graph capture, tight serving loops and harnesses that
+ * forbid hipMalloc: the same block as moe_layer_forward for a layer whose
+ * experts are ALL resident (every entry of layer->host_dev non-NULL), with no
+ * workspace argument and no context.  The intermediate buffers (top-k lists,
+ * bucket offsets and permutations, router logits, h, Y) live in a fixed device
+ * array of MOE_STATIC_WORKSPACE_BYTES inside the library; each GPU the library
+ * runs on holds its own copy of it until the process ends.  The call allocates
+ * nothing: no hipMalloc / hipFree, no events, no streams.  Its output is bit
+ * for bit that of moe_layer_forward on the same inputs.
+ *   - MOE_ERR_WORKSPACE if moe_workspace_bytes(shape) - 256 exceeds the array
+ *     (e.g. the Mixtral-shaped layer fits up to 128 tokens, not 256);
+ *   - every call on a GPU shares that GPU's array: calls that overlap in time
+ *     on one GPU (two streams, two threads) race; serialise them.  Nothing in
+ *     the array has to start at zero and nothing is kept between calls.
+ *   X, residual (nullable), out: as moe_layer_forward. */
+#define MOE_STATIC_WORKSPACE_BYTES (16u << 20)
+size_t moe_static_workspace_bytes(void);
+moe_status moe_layer_forward_static(const moe_shape* shape, const moe_layer_desc* layer,
+                                    const void* X, const void* residual, void* out,
+                                    void* stream);
+
 /* Stack glue (outside the block itself): weightless RMS normalisation of the
  * residual stream, out[t,:] = X[t,:] / sqrt(mean_h X[t,h]^2 + eps), float32
  * arithmetic, one rounding to the storage dtype.  A stack of MoE blocks is

@@ -114,6 +114,9 @@ _lib.moe_destroy.argtypes = [_P]
 _lib.moe_layer_forward.argtypes = [_P, _SH, C.POINTER(moe_layer_desc), C.POINTER(C.c_uint64),
                                    C.POINTER(moe_layer_desc), C.POINTER(C.c_uint64),
                                    _P, _P, _P, _P, _P, C.POINTER(moe_layer_stats)]
+_lib.moe_layer_forward_static.argtypes = [_SH, C.POINTER(moe_layer_desc), _P, _P, _P, _P]
+_lib.moe_static_workspace_bytes.restype = C.c_size_t
+_lib.moe_static_workspace_bytes.argtypes = []
 _lib.moe_stream_totals_get.argtypes = [_P, C.POINTER(moe_stream_totals), C.c_int32]
 _lib.moe_phase_timing.argtypes = [_P, C.c_int32]
 _lib.moe_phase_times_get.argtypes = [_P, C.POINTER(moe_phase_times), C.c_int32]
@@ -134,10 +137,10 @@ _lib.moe_prefetch_hottest.argtypes = [C.POINTER(moe_pending), C.c_int32, C.c_int
 _lib.moe_presched.argtypes = [C.POINTER(moe_presched_costs), C.POINTER(moe_pending), C.c_int32,
                               C.POINTER(moe_pending), C.c_int32, C.POINTER(moe_presched_plan)]
 for _n in ("moe_counter_add", "moe_hot_table", "moe_predict_counts", "moe_presched",
-           "moe_pending_experts", "moe_prefetch_hottest",
+           "moe_pending_experts", "moe_prefetch_hottest", "moe_layer_forward_static",
            "moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_create",
-           "moe_destroy", "moe_layer_forward", "moe_stream_totals_get", "moe_workspace_views",
-           "moe_phase_timing", "moe_phase_times_get", "moe_probe_copy", "moe_probe_read",
+           "moe_destroy", "moe_layer_forward", "moe_layer_forward_static", "moe_stream_totals_get",
+           "moe_workspace_views", "moe_phase_timing", "moe_phase_times_get", "moe_probe_copy", "moe_probe_read",
            "moe_probe_read_nt", "moe_rmsnorm", "moe_set_option", "moe_pack_weights"):
     getattr(_lib, _n).restype = C.c_int32
 
@@ -147,7 +150,8 @@ EXPORTS = ["moe_version", "moe_last_error", "moe_workspace_bytes", "moe_route", 
            "moe_phase_times_get", "moe_probe_copy", "moe_probe_read", "moe_probe_read_nt",
            "moe_rmsnorm", "moe_set_option", "moe_pack_weights",
            "moe_counter_add", "moe_hot_table", "moe_predict_counts", "moe_presched",
-           "moe_ffn_kernel_name", "moe_pending_experts", "moe_prefetch_hottest"]
+           "moe_ffn_kernel_name", "moe_layer_forward_static", "moe_static_workspace_bytes",
+           "moe_pending_experts", "moe_prefetch_hottest"]
 
 
 def _check(st: int):
@@ -377,6 +381,19 @@ def moe_layer_forward(ctx: Context, shape, layer: Layer, X, out, workspace, resi
         _ptr(workspace, "workspace", (torch.uint8,), moe_workspace_bytes(shape)),
         _stream(stream), C.byref(stats) if stats is not None else None))
     return stats.as_dict() if stats is not None else None
+
+
+def moe_static_workspace_bytes() -> int:
+    return _lib.moe_static_workspace_bytes()
+
+
+def moe_layer_forward_static(shape, layer: Layer, X, out, residual=None, stream=None):
+    """moe_layer_forward for an all-resident layer, workspace inside the library."""
+    sd = _storage_dtypes(shape)
+    _check(_lib.moe_layer_forward_static(
+        C.byref(shape), C.byref(layer.desc), _ptr(X, "X", sd, shape.T * shape.H),
+        _ptr(residual, "residual", sd, shape.T * shape.H), _ptr(out, "out", sd, shape.T * shape.H),
+        _stream(stream)))
 
 
 def moe_pack_weights(src: torch.Tensor, dst: torch.Tensor, N: int, K: int, stream=None):

@@ -16,6 +16,7 @@
 // the last kernel that reads the slot) gates the side stream's next overwrite.
 #include "common.h"
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -512,6 +513,98 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
   }
   c->cur_group ^= 1;
   return MOE_OK;
+}
+
+// ---- the block for callers that cannot allocate ---------------------------
+// The workspace of an all-resident layer lives in a fixed device array inside
+// the library.  In host code the array's name is only a stand-in for the
+// symbol: its device address is looked up once per device, with that device
+// current, and that address is what every kernel and copy is handed.
+static __device__ __align__(256) unsigned char scratch[MOE_STATIC_WORKSPACE_BYTES];
+
+namespace moe {
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of this device's copy of `scratch` (every GPU the library runs
+// on holds its own copy at its own address).
+moe_status static_workspace(void** out) {
+  int dev = -1;
+  MOE_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices)
+    return fail(MOE_ERR_UNSUPPORTED, "moe_layer_forward_static: device index %d out of range", dev);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    MOE_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(MOE_ERR_HIP, "moe_layer_forward_static: the scratch symbol has no device address");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MOE_OK;
+}
+
+}  // namespace
+}  // namespace moe
+
+extern "C" size_t moe_static_workspace_bytes(void) { return MOE_STATIC_WORKSPACE_BYTES; }
+
+extern "C" moe_status moe_layer_forward_static(const moe_shape* shape, const moe_layer_desc* layer,
+                                               const void* X, const void* residual, void* out,
+                                               void* stream_) {
+  using namespace moe;
+  moe_status st = check_shape(shape, "moe_layer_forward_static");
+  if (st != MOE_OK) return st;
+  const moe_shape& s = *shape;
+  MOE_REQUIRE(layer && layer->Wr && layer->host_dev,
+              "moe_layer_forward_static: layer without router or expert table");
+  const WorkspaceLayout L = workspace_layout(s);
+  if (L.total > (size_t)MOE_STATIC_WORKSPACE_BYTES)
+    return fail(MOE_ERR_WORKSPACE,
+                "moe_layer_forward_static: this shape needs %zu bytes of workspace, the fixed array "
+                "holds %zu; use moe_layer_forward with a caller-allocated workspace",
+                L.total, (size_t)MOE_STATIC_WORKSPACE_BYTES);
+  if (s.T == 0) return MOE_OK;
+  MOE_REQUIRE(X && out, "moe_layer_forward_static: NULL X or out");
+  ExpertTable tab;
+  GroupList groups;
+  groups.n = 0;
+  for (int e = 0; e < s.E + s.S; ++e) {
+    MOE_REQUIRE(layer->host_dev[e].Wg && layer->host_dev[e].Wu && layer->host_dev[e].Wd,
+                "moe_layer_forward_static: expert %d has a NULL device matrix (every expert must be resident)", e);
+    tab.Wg[e] = layer->host_dev[e].Wg;
+    tab.Wu[e] = layer->host_dev[e].Wu;
+    tab.Wd[e] = layer->host_dev[e].Wd;
+    groups.id[groups.n++] = (uint8_t)e;
+  }
+  void* base = nullptr;
+  st = static_workspace(&base);
+  if (st != MOE_OK) return st;
+  char* w = static_cast<char*>(base);
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  int32_t* topk_idx = reinterpret_cast<int32_t*>(w + L.topk_idx);
+  float* topk_w = reinterpret_cast<float*>(w + L.topk_w);
+  int32_t* count = reinterpret_cast<int32_t*>(w + L.count);
+  int32_t* offset = reinterpret_cast<int32_t*>(w + L.offset);
+  int32_t* perm = reinterpret_cast<int32_t*>(w + L.perm);
+  int32_t* inv_perm = reinterpret_cast<int32_t*>(w + L.inv_perm);
+  const FfnScratch h{w + L.h};
+  float* Y = reinterpret_cast<float*>(w + L.y);
+  // nothing in the workspace has to start at zero: every kernel below writes
+  // what the next one reads (the previous call's contents are simply overwritten)
+  st = launch_route(s, X, layer->Wr, layer->bias, topk_idx, topk_w,
+                    reinterpret_cast<double*>(w + L.logits), stream);
+  if (st != MOE_OK) return st;
+  st = launch_permute(s, topk_idx, count, offset, perm, inv_perm, stream);
+  if (st != MOE_OK) return st;
+  st = launch_ffn_gate_up(s, X, perm, offset, tab, groups, h, stream);
+  if (st != MOE_OK) return st;
+  st = launch_ffn_down(s, h, perm, offset, tab, groups, Y, stream);
+  if (st != MOE_OK) return st;
+  return launch_combine(s, Y, topk_w, inv_perm, residual, out, stream);
 }
 
 extern "C" moe_status moe_set_option(moe_ctx* c, int32_t option, int64_t value) {
