@@ -64,7 +64,19 @@ def parse():
                          "table of a profiling pass under the same budget")
     ap.add_argument("--c5-profile-steps", type=int, default=8)
     ap.add_argument("--c5-tokens", type=int, default=None,
-                    help="c5_stack batch (default: the configuration's 32)")
+                    help="c5_stack batch (default: the shape's own)")
+    ap.add_argument("--c5-shape", default="c5_stack",
+                    choices=["c5_stack", "c4_dsv2lite_prefill", "c6_qwen3_a3b", "c3_finegrained"],
+                    help="c5_stack: layer shape of the streamed stack (default: Mixtral-shaped)")
+    ap.add_argument("--c5-resident", type=int, default=None,
+                    help="c5_stack: resident experts per layer (default: half)")
+    ap.add_argument("--c5-prefetch-n", type=int, default=2,
+                    help="c5_stack: experts prefetched per layer by the fixed-count policies")
+    ap.add_argument("--c5-step-log", action="store_true", help="c5_stack: report wall time per step")
+    ap.add_argument("--c5-repeat", type=int, default=1,
+                    help="c5_stack: run the timed streamed pass this many times, report the last")
+    ap.add_argument("--no-c5-warm", action="store_true",
+                    help="c5_stack: skip the load-time pass that touches every pinned block once")
     ap.add_argument("--no-c5-controls", action="store_true",
                     help="c5_stack: skip the synchronous-copy and three-copies-per-expert reruns")
     ap.add_argument("--layout", default="tiled", choices=["tiled", "row_major"],
@@ -134,14 +146,15 @@ def run_c5(args, torch, B):
     from workloads import get_config, make_layer, make_hidden, make_residency_mask, make_prefetch_noise
     from paper_2509_23638_amd.stack import StreamedStack, noisy_topk_prefetch_mask, _to_torch
 
-    cfg = get_config("c5_stack")
+    cfg = get_config(args.c5_shape)
     if args.c5_tokens:
         cfg = cfg.with_(T=args.c5_tokens)
     NL, NS, T, E = args.c5_layers, args.c5_steps, cfg.T, cfg.E
+    NPF = args.c5_prefetch_n
     sh = B.make_shape(T, cfg.H, E, cfg.k, cfg.F, cfg.S, cfg.dtype, args.layout)
     P = min(args.weight_period, NL)
     hosts = [make_layer(cfg, layer=p, with_hidden=False, threads=16) for p in range(P)]
-    res = [make_residency_mask(cfg, l) for l in range(NL)]
+    res = [make_residency_mask(cfg, l, args.c5_resident) for l in range(NL)]
     ref = StreamedStack(sh, hosts, [[True] * E] * NL, 0, 0, n_layers=NL)
     hot_info = None
     if args.c5_residency == "hot":
@@ -167,7 +180,9 @@ def run_c5(args, torch, B):
                     "tokens_covered_by_hot_table": int(tok[hot].sum()), "tokens_total": int(tok.sum()),
                     "resident_per_layer_min_max": [int(hot.sum(1).min()), int(hot.sum(1).max())]}
         res = [hot[l] for l in range(NL)]
-    stack = StreamedStack(sh, hosts, res, 2, 2, n_layers=NL)
+    stack = StreamedStack(sh, hosts, res, 2, max(NPF, 1), n_layers=NL)
+    if not args.no_c5_warm:
+        stack.warm_host_copies()       # load time: every pinned block crosses the link once
     Xs = [_to_torch(make_hidden(cfg, step=s)).cuda() for s in range(NS)]
 
     # recorded all-resident pass: true router logits of every (step, layer)
@@ -196,7 +211,7 @@ def run_c5(args, torch, B):
             if ns >= NS:
                 continue
             noise = make_prefetch_noise(cfg, nl, ns)
-            masks[s][l] = noisy_topk_prefetch_mask(logits[ns][nl], noise, cfg.k, 2, res[nl])
+            masks[s][l] = noisy_topk_prefetch_mask(logits[ns][nl], noise, cfg.k, NPF, res[nl])
 
     def timed(fn):
         torch.cuda.synchronize()
@@ -212,39 +227,68 @@ def run_c5(args, torch, B):
     costs = B.moe_presched_costs(t_io=1.0, t_g=0.0, t_attn=0.0, beta=0.0, C=0.0, alpha=0.0,
                                  r_hit=0.5, cpu_executor=0)
 
-    def run_streamed():
+    step_log = []
+
+    def run_streamed(want_stats=True):
+        """One pass over all steps.  With want_stats the per-layer hit/miss counts come
+        back (every layer then waits on the host for the router's counts); without, a
+        layer whose non-resident experts are all prefetched never blocks the host."""
         agg = {"n_active": 0, "n_resident": 0, "n_hit": 0, "n_miss": 0, "n_wasted": 0,
                "n_prefetch_issued": 0, "bytes_on_demand": 0, "bytes_prefetch": 0}
         same = True
+        t_prev = time.perf_counter()
         for s in range(NS):
             if args.c5_policy == "noisy_top2":
-                x, st = stack.step(Xs[s], prefetch_masks=masks[s], wrap_prefetch=s + 1 < NS)
+                x, st = stack.step(Xs[s], prefetch_masks=masks[s], wrap_prefetch=s + 1 < NS,
+                                   want_stats=want_stats)
+                st = st if want_stats else []
             else:
                 if agg["n_prefetch_issued"]:
                     # hit rate of the prefetches so far, as the Timer/Counter would report it
                     costs.r_hit = agg["n_hit"] / agg["n_prefetch_issued"]
                 pol = {"gate_top2": "gate_topn", "presched": "presched", "none": "none"}[args.c5_policy]
-                x, st = stack.step_online(Xs[s], pol, costs=costs, n_prefetch=2,
+                x, st = stack.step_online(Xs[s], pol, costs=costs, n_prefetch=NPF,
                                           wrap_prefetch=False)
             for d in st:
                 for k_ in agg:
                     agg[k_] += d[k_]
             same = same and bool(torch.equal(x.view(torch.int16), finals[s].view(torch.int16)))
+            if args.c5_step_log:      # per-step wall time (the comparison above synchronises)
+                now = time.perf_counter()
+                step_log.append(round((now - t_prev) * 1e3, 3))
+                t_prev = now
         return agg, same
 
     run_ref()
     t_c, _ = timed(run_ref)
     # Timer inputs of PreSched, measured: one layer's compute, one expert's load
     t_layer = t_c / (NS * NL)
+    # (one untimed streamed step, prefetches included: it also absorbs the one-time cost
+    # of the first cross-stream waits, ~80 ms in a fresh process)
+    stack.step(Xs[0], prefetch_masks=masks[0], want_stats=False)
+    torch.cuda.synchronize()
+    # the load time of one expert, from a step whose copies run alone on the link
+    stack.ctx.set_sync_copies(True)
     stack.ctx.stream_totals(reset=True)
-    stack.step(Xs[0], want_stats=False)
+    stack.step(Xs[0], prefetch_masks=masks[0], want_stats=False)
     torch.cuda.synchronize()
     cal = stack.ctx.stream_totals(reset=True)
+    stack.ctx.set_sync_copies(False)
     costs.t_io = cal["copy_ms"] * 1e-3 / max(1, cal["n_copies"])
     costs.t_g = t_layer / E
     costs.t_attn = t_layer          # the only time per layer the link has no on-demand work
-    t_wall, (agg, same) = timed(run_streamed)
-    tot = stack.ctx.stream_totals(reset=True)
+    # hit / miss accounting from an untimed pass with stats; the timed passes run without
+    # (the fixed-mask policy then needs no host wait where everything was prefetched; the
+    # online policies read predicted counts back every layer either way)
+    _, (agg, same0) = timed(run_streamed)
+    stack.ctx.stream_totals(reset=True)
+    fast = args.c5_policy == "noisy_top2"
+    earlier = []
+    for rep in range(args.c5_repeat):
+        t_wall, (agg_t, same) = timed(lambda: run_streamed(want_stats=not fast))
+        same = same and same0
+        tot = stack.ctx.stream_totals(reset=True)
+        earlier.append({"T_wall_s": t_wall, "T_x_s": tot["copy_ms"] * 1e-3})
     t_x = tot["copy_ms"] * 1e-3
     sched_log = dict(stack.sched_log)
     if args.no_c5_controls:
@@ -252,24 +296,24 @@ def run_c5(args, torch, B):
         t_wall3, same3, tot3 = None, True, {"bytes": 0, "copy_ms": 0.0}
     else:
         stack.ctx.set_sync_copies(True)
-        t_sync, (agg2, same2) = timed(run_streamed)
+        t_sync, (agg2, same2) = timed(lambda: run_streamed(want_stats=not fast))
         tot2 = stack.ctx.stream_totals(reset=True)
         stack.ctx.set_sync_copies(False)
         # Section 4.4's sub-tensor granularity: three copies per expert, phase 1 gated on gate+up
         stack.ctx.set_copy_split(3)
-        t_wall3, (agg3, same3) = timed(run_streamed)
+        t_wall3, (agg3, same3) = timed(lambda: run_streamed(want_stats=not fast))
         tot3 = stack.ctx.stream_totals(reset=True)
         stack.ctx.set_copy_split(1)
 
     tokens = T * NS
     res_json = {
-        "metric": f"streamed MoE stack decode tokens/sec ({NL}-layer Mixtral-shaped stack, batch {T}, "
-                  "half of the experts in pinned host memory)",
+        "metric": f"streamed MoE stack tokens/sec ({NL}-layer {args.c5_shape}-shaped stack, batch {T}, "
+                  f"{int(np.sum(res[0]))} of {E} routed experts per layer resident, the rest in pinned host memory)",
         "value": tokens / t_wall, "unit": "tokens/s", "n_gpus": 1, "steps": NS, "warmup": 0,
         "ms_per_step": t_wall / NS * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"c5_stack: {NL} layers x {NS} decode steps, T={T}, weights repeat "
-                               f"with period {P} layers, 2 on-demand + 2x2 prefetch slots, "
+        "config": {"workload": f"c5_stack ({args.c5_shape} layers): {NL} layers x {NS} steps, T={T}, weights repeat "
+                               f"with period {P} layers, 2 on-demand + 2x{max(NPF, 1)} prefetch slots, "
                                f"{args.layout} weight layout, prefetch policy {args.c5_policy}, "
                                f"{args.c5_residency} residency"},
         "prefetch": {"policy": args.c5_policy, "issued": agg["n_prefetch_issued"], "hits": agg["n_hit"],
@@ -299,6 +343,7 @@ def run_c5(args, torch, B):
             if tot3["copy_ms"] else None},
         "stats": agg,
         "bitwise_equal_to_all_resident": bool(same and same2 and same3),
+        "timed_passes": earlier, "step_wall_ms": step_log or None,
     }
     ref.close()
     stack.close()

@@ -236,9 +236,10 @@ typedef struct {
  * After the on-demand copies, copies of `host_prefetch_next_mask`'s experts of
  * `next_layer` are queued into the next-layer prefetch group; after the layer
  * the two groups swap roles.  Shared experts must be resident.
- * If any routed expert is non-resident the call waits (on the host) for the
- * router's counts before it can queue copies; with everything resident it
- * never blocks.
+ * If a routed expert is neither resident nor in a prefetch slot for this
+ * layer, or if stats are requested, the call waits (on the host) for the
+ * router's counts before it can queue copies; with every expert resident or
+ * prefetched and stats == NULL it never blocks.
  *   out = block output (+ residual if given), [T,H] storage dtype.
  *   host_resident_mask / host_prefetch_next_mask: HOST words, ceil(E/64) each;
  *     NULL resident mask = all resident; NULL prefetch mask = none.

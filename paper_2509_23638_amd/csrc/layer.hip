@@ -16,6 +16,7 @@
 // the last kernel that reads the slot) gates the side stream's next overwrite.
 #include "common.h"
 
+#include <algorithm>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -85,6 +86,10 @@ namespace {
 
 moe_status make_slot(Slot& s, size_t bytes) {
   MOE_HIP(hipMalloc(reinterpret_cast<void**>(&s.mem), bytes));
+  // touch the slot now: the first write into fresh device memory pays for its
+  // page mappings (measured: 78 ms for four 336 MiB slots inside the first
+  // decode step that used them), and creation is the place for that
+  MOE_HIP(hipMemset(s.mem, 0, bytes));
   MOE_HIP(hipEventCreateWithFlags(&s.copied_gu, hipEventDisableTiming));
   MOE_HIP(hipEventCreateWithFlags(&s.released, hipEventDisableTiming));
   return MOE_OK;
@@ -400,10 +405,27 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
     if (st != MOE_OK) return st;
     PHASE_MARK(4);
   } else {
-    // the host must know which experts are active before it can queue copies
-    MOE_HIP(hipMemcpyAsync(c->host_counts, count, s.E * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
-    MOE_HIP(hipEventRecord(c->ev_counts, stream));
-    MOE_HIP(hipEventSynchronize(c->ev_counts));
+    // The host must know which experts are active before it can queue copies --
+    // unless there is nothing it could have to copy: every non-resident expert
+    // already sits in a prefetch slot for this layer.  Then the call does not
+    // wait for the router (the kernels skip empty buckets by themselves, so every
+    // expert is simply listed), which keeps the compute stream fed across layers;
+    // a caller that asks for stats still gets the exact counts and pays the wait.
+    bool covered = stats == nullptr;
+    if (covered) {
+      bool in_slot[MOE_MAX_E] = {};
+      for (const Slot& sl : cur)
+        if (sl.valid && sl.layer_id == layer->layer_id && sl.expert >= 0 && sl.expert < s.E)
+          in_slot[sl.expert] = true;
+      for (int e = 0; e < s.E; ++e) covered = covered && (bit(host_resident_mask, e) || in_slot[e]);
+    }
+    if (covered) {
+      for (int e = 0; e < s.E; ++e) c->host_counts[e] = 1;
+    } else {
+      MOE_HIP(hipMemcpyAsync(c->host_counts, count, s.E * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+      MOE_HIP(hipEventRecord(c->ev_counts, stream));
+      MOE_HIP(hipEventSynchronize(c->ev_counts));
+    }
     int n_active = 0, n_res = 0, n_hit = 0, n_miss = 0, n_wasted = 0;
     int hit_slot[MOE_MAX_E];
     std::vector<int> hits, misses;
@@ -438,42 +460,94 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
                   n_miss);
     for (int sx = 0; sx < s.S; ++sx) res_groups.id[res_groups.n++] = (uint8_t)(s.E + sx);
 
-    // resident experts first: they need nothing from the link
-    st = launch_ffn_gated(s, X, perm, offset, tab, res_groups, Y, h, stream, nullptr, nullptr, nullptr);
-    if (st != MOE_OK) return st;
-    // prefetched experts: their copies were queued during the previous layer
+    // Prefetched experts: their copies were queued during the previous layer, in
+    // slot order on the one side stream, so the hit in the highest slot was copied
+    // last and once its bytes have landed so have the others'.
+    GroupList hit_groups;
+    hit_groups.n = 0;
+    Slot* newest = nullptr;
+    int newest_at = -1;
     for (int e : hits) {
       Slot& sl = cur[hit_slot[e]];
       tab.Wg[e] = sl.mem;
       tab.Wu[e] = sl.mem + mb;
       tab.Wd[e] = sl.mem + 2 * mb;
-      GroupList one;
-      one.n = 1;
-      one.id[0] = (uint8_t)e;
-      st = launch_ffn_gated(s, X, perm, offset, tab, one, Y, h, stream,
-                            sl.gu_pending ? sl.copied_gu : sl.copied, sl.copied, nullptr);
+      hit_groups.id[hit_groups.n++] = (uint8_t)e;
+      if (hit_slot[e] > newest_at) {
+        newest_at = hit_slot[e];
+        newest = &sl;
+      }
+    }
+    // They join the residents' launch when they have already landed (as good as
+    // resident), and also when a launch of their own could not fill the chip
+    // (small experts: a few tens of work items cost two under-filled launches,
+    // more than waiting for a copy that was queued a whole layer ago); the joint
+    // launch then waits for the newest of their copies.  Large experts keep the
+    // order "residents first, streamed experts behind their copies".
+    bool hits_joined = false;
+    hipEvent_t join_gu = nullptr, join_d = nullptr;
+    if (newest) {
+      const bool landed = !newest->copied || hipEventQuery(newest->copied) == hipSuccess;
+      const bool small = (size_t)hit_groups.n * 3 * mb < ((size_t)64 << 20);
+      hits_joined = landed || small;
+      if (hits_joined) {
+        for (int i = 0; i < hit_groups.n; ++i) res_groups.id[res_groups.n++] = hit_groups.id[i];
+        if (!landed) {
+          join_gu = newest->gu_pending ? newest->copied_gu : newest->copied;
+          join_d = newest->copied;
+        }
+      }
+    }
+
+    // resident experts first: they need nothing from the link
+    st = launch_ffn_gated(s, X, perm, offset, tab, res_groups, Y, h, stream, join_gu, join_d, nullptr);
+    if (st != MOE_OK) return st;
+    // hits still in flight: ONE grouped launch behind the newest of their copies
+    // (sub-tensor mode: its gate and up projections landing gates the first
+    // phase); a launch per expert costs more in launch and fill overhead than it
+    // could win back
+    if (newest && !hits_joined) {
+      st = launch_ffn_gated(s, X, perm, offset, tab, hit_groups, Y, h, stream,
+                            newest->gu_pending ? newest->copied_gu : newest->copied,
+                            newest->copied, nullptr);
       if (st != MOE_OK) return st;
+    }
+    for (int e : hits) {
+      Slot& sl = cur[hit_slot[e]];
       MOE_HIP(hipEventRecord(sl.released, stream));
       sl.has_release = true;
     }
-    // on-demand loads, through the double buffer, ahead of any new prefetch
-    for (int e : misses) {
-      Slot& sl = c->ondemand[c->od_next];
-      c->od_next = (c->od_next + 1) % (int)c->ondemand.size();
-      st = queue_copy(c, s, sl, layer->host_pinned[e], layer->layer_id, e, stream);
+    // on-demand loads, through the double buffer, ahead of any new prefetch.
+    // Large experts run one launch each, as soon as their own copy has landed
+    // (the next copy flies meanwhile); small ones are copied a buffer-full at a
+    // time and run as one launch behind the last of those copies.
+    const size_t per_launch = (3 * mb < ((size_t)32 << 20)) ? c->ondemand.size() : 1;
+    for (size_t m0 = 0; m0 < misses.size(); m0 += per_launch) {
+      GroupList batch;
+      batch.n = 0;
+      Slot* last = nullptr;
+      std::vector<Slot*> used;
+      for (size_t m = m0; m < std::min(misses.size(), m0 + per_launch); ++m) {
+        const int e = misses[m];
+        Slot& sl = c->ondemand[c->od_next];
+        c->od_next = (c->od_next + 1) % (int)c->ondemand.size();
+        st = queue_copy(c, s, sl, layer->host_pinned[e], layer->layer_id, e, stream);
+        if (st != MOE_OK) return st;
+        tab.Wg[e] = sl.mem;
+        tab.Wu[e] = sl.mem + mb;
+        tab.Wd[e] = sl.mem + 2 * mb;
+        batch.id[batch.n++] = (uint8_t)e;
+        last = &sl;
+        used.push_back(&sl);
+        if (stats) stats->bytes_on_demand += (int64_t)(3 * mb);
+      }
+      st = launch_ffn_gated(s, X, perm, offset, tab, batch, Y, h, stream,
+                            last->gu_pending ? last->copied_gu : last->copied, last->copied, nullptr);
       if (st != MOE_OK) return st;
-      tab.Wg[e] = sl.mem;
-      tab.Wu[e] = sl.mem + mb;
-      tab.Wd[e] = sl.mem + 2 * mb;
-      GroupList one;
-      one.n = 1;
-      one.id[0] = (uint8_t)e;
-      st = launch_ffn_gated(s, X, perm, offset, tab, one, Y, h, stream,
-                            sl.gu_pending ? sl.copied_gu : sl.copied, sl.copied, nullptr);
-      if (st != MOE_OK) return st;
-      MOE_HIP(hipEventRecord(sl.released, stream));
-      sl.has_release = true;
-      if (stats) stats->bytes_on_demand += (int64_t)(3 * mb);
+      for (Slot* sl : used) {
+        MOE_HIP(hipEventRecord(sl->released, stream));
+        sl->has_release = true;
+      }
     }
     if (stats) {
       stats->n_active = n_active;

@@ -45,6 +45,7 @@ class StreamedStack:
                 res = e >= E or self.resident[l][e]
                 (need_dev if res else need_pin)[l % P][e] = True
         self._dev, self._pin, self._router = [], [], []
+        self._pin_blocks = []
         for p, L in enumerate(layers_host):
             dev = {n: [None] * (E + S) for n in ("Wg", "Wu", "Wd")}
             pin = {n: [None] * (E + S) for n in ("Wg", "Wu", "Wd")}
@@ -67,6 +68,7 @@ class StreamedStack:
                 if need_pin[p][e]:
                     # the three matrices back to back: one copy moves the expert
                     blk = torch.empty(3 * ts[0].numel(), dtype=ts[0].dtype, pin_memory=True)
+                    self._pin_blocks.append(blk)
                     for i, (n, t) in enumerate(zip(("Wg", "Wu", "Wd"), ts)):
                         v = blk[i * t.numel():(i + 1) * t.numel()].view(t.shape)
                         v.copy_(t)
@@ -89,6 +91,19 @@ class StreamedStack:
 
     def close(self):
         self.ctx.close()
+
+    def warm_host_copies(self):
+        """One host-to-device copy of every pinned expert block into a scratch
+        buffer, meant for load time (outside any timed region): the first
+        transfer out of freshly pinned pages is slower than the later ones, and a
+        serving process should not pay that inside its first decode steps."""
+        if not self._pin_blocks:
+            return
+        scratch = torch.empty(max(b.numel() for b in self._pin_blocks),
+                              dtype=self._pin_blocks[0].dtype, device="cuda")
+        for b in self._pin_blocks:
+            scratch[:b.numel()].copy_(b, non_blocking=True)
+        torch.cuda.synchronize()
 
     def layer_forward(self, l: int, x_in: torch.Tensor, out: torch.Tensor, residual=None,
                       prefetch_next_mask=None, next_l: Optional[int] = None, want_stats=True):

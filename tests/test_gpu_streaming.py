@@ -119,6 +119,35 @@ def test_free_running_stack_stays_close_to_oracle(B, layers):
     stack.close()
 
 
+@pytest.mark.parametrize("layout", ["row_major", "tiled"])
+def test_fully_prefetched_layers_need_no_host_wait_and_keep_the_bits(B, layers, layout):
+    """When every non-resident expert of a layer sits in a prefetch slot and no
+    stats are asked for, the layer is queued without waiting for the router's
+    counts (every expert is listed, the kernels skip empty buckets).  Same bits
+    as the all-resident stack, step after step, with the prefetch for layer 0 of
+    the next step issued by the last layer."""
+    from paper_2509_23638_amd.stack import StreamedStack
+    sh = B.make_shape(CFG.T, CFG.H, CFG.E, CFG.k, CFG.F, CFG.S, CFG.dtype, layout)
+    res = [make_residency_mask(CFG, l) for l in range(CFG.layers)]
+    ref_stack = StreamedStack(sh, layers, [[True] * CFG.E] * CFG.layers, 0, 0)
+    stack = StreamedStack(sh, layers, res, 2, CFG.E // 2)          # a slot for every non-resident expert
+    pf = [~res[(l + 1) % CFG.layers] for l in range(CFG.layers)]
+    for step in range(CFG.steps):
+        X = to_dev(make_hidden(CFG, step=step))
+        want, _ = ref_stack.step(X, want_stats=False)
+        want = want.clone()
+        got, stats = stack.step(X, prefetch_masks=pf, wrap_prefetch=True, want_stats=False)
+        torch.cuda.synchronize()
+        assert all(st is None for st in stats)
+        assert torch.equal(got.view(torch.int16), want.view(torch.int16)), f"step {step}"
+    tot = stack.ctx.stream_totals()
+    # step 0 / layer 0 found nothing prefetched (on-demand loads of its active experts); every
+    # later layer found all four of its non-resident experts in slots
+    assert tot["n_copies"] >= (CFG.steps * CFG.layers - 1) * (CFG.E // 2)
+    stack.close()
+    ref_stack.close()
+
+
 def test_rmsnorm_matches_oracle(B):
     sh = B.make_shape(CFG.T, CFG.H, CFG.E, CFG.k, CFG.F, CFG.S, CFG.dtype)
     X = make_hidden(CFG, step=9)
