@@ -51,7 +51,7 @@ constexpr int kFragBytes = MOE_WAVE * 16;        // one B fragment in LDS
 // still read once.  One LDS buffer holds TB * 4 fragments.
 constexpr int buf_bytes(int tb) { return tb * kStepsPerChunk * kFragBytes; }
 
-enum { kGateUp = 0, kDown = 1, kDownHalves = 2 };
+enum { kGateUp = 0, kDown = 1, kDownHalves = 2, kDownNarrow = 3 };
 
 struct FfnArgs {
   const uint16_t* act;    // gate/up: X [T,H]; down: h [rows,F]
@@ -63,6 +63,8 @@ struct FfnArgs {
   int N;                  // output width
   int tiled;              // weights are in the tiled layout (see moe_weight_layout)
   int interleave;         // tiled kernels: deal work items to the XCDs round-robin (see tile_order)
+  int heavy_first;        // stream kernels: walk groups and passes backwards (see ffn_stream_kernel)
+  int split_tail;         // eight-wave tiled kernel: cut the items of a partly filled last round (see TileSplit)
 };
 
 // Element offset of the 16 bytes lane (r, g) feeds the MFMA with for weight tile
@@ -88,6 +90,11 @@ __device__ __forceinline__ float silu_f(float z) {
 // activation fragment read from LDS for four MFMAs instead of two, which is
 // what a compute-heavy batch (prefill) needs.
 //
+// kDownNarrow: the down projection with ONE tile per wave (a workgroup owns 64
+// rows of Wd): twice the workgroups of half the size, for shapes whose few
+// hundred 128-row workgroups would fill the chip's workgroup slots one and a
+// bit times (the last, nearly empty round costs as much as a full one).
+//
 // kDownHalves: the wave's two tiles are the SAME 16 rows of Wd over the first
 // and the second half of the contraction, summed at the end.  A workgroup then
 // owns 64 rows instead of 128, so a Mixtral-shaped down projection has twice
@@ -98,7 +105,7 @@ struct Streamer {
   static constexpr bool kHalves = MODE == kDownHalves;
   static constexpr int NH = kHalves ? 2 : 1;          // activation positions staged per chunk
   static constexpr int kBufBytes = NH * buf_bytes(TB);
-  static constexpr int NA = 2 * RT;
+  static constexpr int NA = MODE == kDownNarrow ? 1 : 2 * RT;
   int half_chunks = 0;    // kDownHalves: chunks per half of the contraction
   const FfnArgs& a;
   const uint16_t* w[NA];  // this lane's first element in each weight tile
@@ -231,7 +238,7 @@ template <int MODE, int NT, int TB, int RT, bool ONCE>
 __device__ __forceinline__ void ffn_block(const FfnArgs& a, const uint16_t* W0, const uint16_t* W1,
                                           int n0, int r0, int row_end, int shared_base,
                                           unsigned char* lds) {
-  constexpr int NA = 2 * RT;
+  constexpr int NA = MODE == kDownNarrow ? 1 : 2 * RT;
   Streamer<MODE, NT, TB, RT, ONCE> st(a);
   st.lds = lds;
   st.lane = threadIdx.x & (MOE_WAVE - 1);
@@ -244,6 +251,9 @@ __device__ __forceinline__ void ffn_block(const FfnArgs& a, const uint16_t* W0, 
     if (MODE == kGateUp) {
       nrow[i] = n0 + (st.wave * RT + (i >> 1)) * 16;
       st.w[i] = ((i & 1) ? W1 : W0) + weight_lane_offset(a.tiled, nrow[i] / 16, a.K, st.lane);
+    } else if (MODE == kDownNarrow) {
+      nrow[i] = n0 + st.wave * 16;
+      st.w[i] = W0 + weight_lane_offset(a.tiled, nrow[i] / 16, a.K, st.lane);
     } else if (MODE == kDownHalves) {
       st.half_chunks = a.K / kChunk / 2;
       nrow[i] = n0 + st.wave * 16;
@@ -322,7 +332,14 @@ __global__ __launch_bounds__(kThreads) void ffn_stream_kernel(FfnArgs a, ExpertT
                                                               GroupList groups) {
   constexpr int kTokBlock = 16 * TB;
   __shared__ __attribute__((aligned(16))) unsigned char lds[2 * (MODE == kDownHalves ? 2 : 1) * buf_bytes(TB)];
-  const int e = groups.id[blockIdx.y];
+  // Workgroups are handed out in grid order, and the ones that take longest
+  // should go first: later passes over a bucket exist only for the fullest
+  // buckets, and the shared experts (listed last) see every token.  So when a
+  // launch has either, the grid is walked backwards in both of those dimensions
+  // (fine-grained layer, 128 tokens: gate/up 80 -> 74 us; with equal experts and
+  // a single pass the forward order measured 3 % faster and stays).
+  const int e = groups.id[a.heavy_first ? gridDim.y - 1 - blockIdx.y : blockIdx.y];
+  const int pass = a.heavy_first ? gridDim.z - 1 - blockIdx.z : blockIdx.z;
   int row_begin, row_end, shared_base = -1;
   if (e < a.E) {
     row_begin = a.offset[e];
@@ -332,7 +349,7 @@ __global__ __launch_bounds__(kThreads) void ffn_stream_kernel(FfnArgs a, ExpertT
     row_end = row_begin + a.T;
     shared_base = row_begin;
   }
-  const int r0 = row_begin + blockIdx.z * kTokBlock;
+  const int r0 = row_begin + pass * kTokBlock;
   if (r0 >= row_end) return;
   const int nt = (min(row_end - r0, kTokBlock) + 15) / 16;
   const uint16_t *W0, *W1;
@@ -341,7 +358,7 @@ __global__ __launch_bounds__(kThreads) void ffn_stream_kernel(FfnArgs a, ExpertT
     W0 = static_cast<const uint16_t*>(tab.Wg[e]);
     W1 = static_cast<const uint16_t*>(tab.Wu[e]);
     n0 = blockIdx.x * (kWaves * 16 * RT);
-  } else if (MODE == kDownHalves) {
+  } else if (MODE == kDownHalves || MODE == kDownNarrow) {
     W0 = W1 = static_cast<const uint16_t*>(tab.Wd[e]);
     n0 = blockIdx.x * (kWaves * 16);
   } else {
@@ -349,7 +366,7 @@ __global__ __launch_bounds__(kThreads) void ffn_stream_kernel(FfnArgs a, ExpertT
     n0 = blockIdx.x * (kWaves * 32 * RT);
   }
   // whole bucket in this one pass: nobody else reads these weight rows
-  if (blockIdx.z == 0 && row_end - r0 <= kTokBlock)
+  if (pass == 0 && row_end - r0 <= kTokBlock)
     ffn_block_sized<MODE, TB, RT, true>(nt, a, W0, W1, n0, r0, row_end, shared_base, lds);
   else
     ffn_block_sized<MODE, TB, RT, false>(nt, a, W0, W1, n0, r0, row_end, shared_base, lds);
@@ -481,6 +498,20 @@ __device__ __forceinline__ TileItem tile_item(const GroupList& groups, const Til
   it.r0 = pl.begin[g] + (blk - pl.first[g]) * ROWS;
   it.row_end = pl.begin[g] + pl.rows[g];
   it.single = pl.rows[g] <= ROWS;
+  return it;
+}
+
+// Part `part` of `parts` of an item: the same weight slab over a share of the
+// block's token tiles (see TileSplit).  Parts past the block's last tile are
+// empty: r0 == row_end, nothing is stored and every load is clamped to the
+// bucket's last row.
+__device__ __forceinline__ TileItem tile_item_part(TileItem it, int rows_per_block, int part, int parts) {
+  const int tiles = (min(it.row_end - it.r0, rows_per_block) + 15) / 16;
+  const int per = (tiles + parts - 1) / parts;
+  const int block_end = min(it.row_end, it.r0 + rows_per_block);
+  it.r0 = min(it.r0 + part * per * 16, block_end);
+  it.row_end = min(block_end, it.r0 + per * 16);
+  it.single = 0;   // its weights are read by the other parts too
   return it;
 }
 
@@ -758,6 +789,47 @@ __device__ __forceinline__ TileOrder tile_order(int total, int xcd, bool interle
     o.count = max(0, min(per_xcd, total - o.base));
   }
   return o;
+}
+
+// The last round of a persistent loop.  A workgroup of an XCD walks items
+// local, local + stride, ...: with `count` items per XCD the last round holds
+// count mod stride of them, and costs a whole item's time however few they are
+// (880 items of a prefill layer over 256 workgroups: the fourth round is 44 %
+// full).  So the items of a partly filled last round are cut into 2 or 4 parts
+// along the token tiles of their block (same weights, a share of the rows: the
+// variants for short blocks run them), as many as keep the parts within one
+// round.  Splitting never changes a sum: every output row is still one
+// workgroup's fixed-order accumulation over the whole contraction.
+struct TileSplit {
+  int full;    // walk positions below this are whole items
+  int parts;   // positions from `full` on are parts: item full + (n - full) / parts
+  int count;   // walk positions in all
+  __device__ __forceinline__ int item(int n) const { return n < full ? n : full + (n - full) / parts; }
+  __device__ __forceinline__ int part(int n) const { return n < full ? -1 : (n - full) % parts; }
+};
+__device__ __forceinline__ TileSplit tile_split(int count, int stride, bool allow) {
+  TileSplit sp;
+  const int rem = count % stride;
+  sp.full = count;
+  sp.parts = 1;
+  sp.count = count;
+  if (allow && rem > 0 && count > stride) {
+    // cost of the last round in item times: ceil(parts * rem / stride) / parts
+    int best = 4, parts = 1;   // in quarters
+    for (int f = 2; f <= 4; f *= 2) {
+      const int c = ((f * rem + stride - 1) / stride) * (4 / f);
+      if (c < best) {
+        best = c;
+        parts = f;
+      }
+    }
+    if (parts > 1) {
+      sp.full = count - rem;
+      sp.parts = parts;
+      sp.count = sp.full + parts * rem;
+    }
+  }
+  return sp;
 }
 
 // Persistent workgroups, one per compute unit (the 144 KiB ring allows no
@@ -1415,11 +1487,17 @@ __global__ __launch_bounds__(kWideThreads, 1) void ffn_wide_kernel(FfnArgs a, Ex
   const int xcd = blockIdx.x & 7, stride = gridDim.x >> 3;   // grid is a multiple of 8
   int local = blockIdx.x >> 3;
   const TileOrder order = tile_order(total, xcd, a.interleave && (plan.sizes & (plan.sizes - 1)) != 0);
-  if (local >= order.count) return;
+  const TileSplit split = tile_split(order.count, stride, a.split_tail != 0);
+  if (local >= split.count) return;
   const int lane = threadIdx.x & (MOE_WAVE - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE);   // uniform: a scalar register
+  auto item_at = [&](int n) {
+    TileItem t = tile_item<kWideRows>(groups, plan, order.item(split.item(n)), slabs);
+    const int part = split.part(n);
+    return part < 0 ? t : tile_item_part(t, kWideRows, part, split.parts);
+  };
 
-  TileItem it = tile_item<kWideRows>(groups, plan, order.item(local), slabs);
+  TileItem it = item_at(local);
   const ActRsrc rsrc = wide_resource(a, act_rows);
   uint32_t src[kWideFetch];
   {
@@ -1430,9 +1508,9 @@ __global__ __launch_bounds__(kWideThreads, 1) void ffn_wide_kernel(FfnArgs a, Ex
     for (int q = 0; q < kWideTLead; ++q) wide_fetch(rsrc, src, q, wave, ring);
   }
   while (true) {
-    const bool has_next = local + stride < order.count;
+    const bool has_next = local + stride < split.count;
     TileItem nxt = it;
-    if (has_next) nxt = tile_item<kWideRows>(groups, plan, order.item(local + stride), slabs);
+    if (has_next) nxt = item_at(local + stride);
     const int tiles = (min(it.row_end - it.r0, kWideRows) + 15) / 16;
     // gate/up weights of an expert with a single block: non-temporal.  (For the
     // down projection the hint measured slower in this kernel.)
@@ -1477,6 +1555,12 @@ int max_row_blocks(const moe_shape& s, int block_rows) {
 // weight stream; the kernel then uses it if the buckets are uneven.  (For the
 // down projection, whose activations are the much larger h, it measured slower
 // at every size.)  MOE_TUNE_INTERLEAVE=0|1 overrides (tuning builds only).
+// MOE_TUNE_SPLIT=0 switches the cutting of last-round items off (tuning builds only).
+int split_allowed() {
+  static const char* env = tune_env("MOE_TUNE_SPLIT");
+  return !(env && env[0] == '0');
+}
+
 int interleave_allowed(long long act_bytes) {
   static const char* env = tune_env("MOE_TUNE_INTERLEAVE");
   if (env && (env[0] == '0' || env[0] == '1')) return env[0] == '1';
@@ -1776,6 +1860,9 @@ __global__ __launch_bounds__(kThreads) void ffn_f32_kernel(F32Args a, ExpertTabl
 
 // Which kernel serves a phase.  Gate/up and down choose separately:
 //   kStream64   the stream kernel, 64-row passes, one weight tile per wave and matrix
+//               (down: one tile per wave, 64 weight rows per workgroup -- with
+//               128-row workgroups a fine-grained layer of some thirty active
+//               experts has barely more workgroups than the chip has slots)
 //   kStream128  the stream kernel, 128-row passes (an expert with up to 128
 //               rows still has its weights read once)
 //   kTile       the tiled kernel (persistent, both operands through LDS)
@@ -1837,6 +1924,13 @@ Variant down_variant(const moe_shape& s) {
   const Variant v = rows_rule(s);
   if (v != kStream64) return v;
   const double rows = (double)s.T * s.k / s.E;
+  // wide experts at decode sizes: from about a dozen rows per expert the small
+  // tiled kernel's ring streams the down projection faster than the halved
+  // stream kernel (Mixtral shape: 146 against 150 us at 64 tokens, 145 against
+  // 150 at 48, equal at 32, slower below)
+  if (tile_kernel_fits(s) && s.T <= 64 && rows >= 12.0 && s.H / 128 >= 32 &&
+      (long)(s.E + s.S) * (s.H / 128) >= 256)
+    return kTile;
   // split-K exists to fill the chip when few experts are active; with many
   // experts the halved stream kernel already has thousands of workgroups and
   // measured 9 % faster (128 experts of 2048 x 768, four rows each)
@@ -1855,14 +1949,16 @@ moe_status launch_ffn_gate_up(const moe_shape& s, const void* X, const int32_t* 
   void* h = scratch.h;
   if (s.dtype == MOE_BF16) {
     FfnArgs gu{static_cast<const uint16_t*>(X), perm, offset, h, s.T, s.k, s.E, A, s.H, s.F,
-               s.weight_layout == MOE_TILED, interleave_allowed((long long)s.T * s.H * 2)};
+               s.weight_layout == MOE_TILED, interleave_allowed((long long)s.T * s.H * 2), 0, split_allowed()};
     const Variant v = gate_up_variant(s, groups.n);
     if (v == kTile && tile_kernel_fits(s)) {
       return launch_tile<kGateUp>(s, gu, tab, groups, stream, wide_form(s, 0));
     } else if (v != kStream64) {
+      gu.heavy_first = s.S > 0 || s.T > 128;
       hipLaunchKernelGGL((ffn_stream_kernel<kGateUp, 8, 1>), dim3(s.F / (kWaves * 16), groups.n, (s.T + 127) / 128),
                          dim3(kThreads), 0, stream, gu, tab, groups);
     } else {
+      gu.heavy_first = s.S > 0 || s.T > 64;
       hipLaunchKernelGGL((ffn_stream_kernel<kGateUp, 4, 1>), dim3(s.F / (kWaves * 16), groups.n, (s.T + 63) / 64),
                          dim3(kThreads), 0, stream, gu, tab, groups);
     }
@@ -1886,7 +1982,8 @@ moe_status launch_ffn_down(const moe_shape& s, const FfnScratch& scratch, const 
   const void* h = scratch.h;
   if (s.dtype == MOE_BF16) {
     FfnArgs dn{static_cast<const uint16_t*>(h), perm, offset, Y, s.T, s.k, s.E, A, s.F, s.H,
-               s.weight_layout == MOE_TILED, 0};   // h is too large to share between the XCDs' L2s
+               s.weight_layout == MOE_TILED, 0,    // h is too large to share between the XCDs' L2s
+               s.S > 0 || s.T > 64, split_allowed()};
     const Variant v = down_variant(s);
     if (v == kTile && tile_kernel_fits(s)) {
       return launch_tile<kDown>(s, dn, tab, groups, stream, wide_form(s, 1));
@@ -1901,7 +1998,7 @@ moe_status launch_ffn_down(const moe_shape& s, const FfnScratch& scratch, const 
       hipLaunchKernelGGL((ffn_stream_kernel<kDown, 8, 1>), dim3(s.H / (kWaves * 32), groups.n, (s.T + 127) / 128),
                          dim3(kThreads), 0, stream, dn, tab, groups);
     } else {
-      hipLaunchKernelGGL((ffn_stream_kernel<kDown, 4, 1>), dim3(s.H / (kWaves * 32), groups.n, (s.T + 63) / 64),
+      hipLaunchKernelGGL((ffn_stream_kernel<kDownNarrow, 4, 1>), dim3(s.H / (kWaves * 16), groups.n, (s.T + 63) / 64),
                          dim3(kThreads), 0, stream, dn, tab, groups);
     }
   } else {
