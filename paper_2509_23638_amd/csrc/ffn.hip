@@ -620,23 +620,121 @@ __device__ __forceinline__ void tile_fetch(const uint16_t* const (&src)[kFetchPe
   }
 }
 
+// ---- general form: eight waves --------------------------------------------
+// With one wave per SIMD a stage is a serial chain (wait, barrier, fetch issue,
+// operand reads, matrix instructions) that nothing overlaps: measured on a
+// Mixtral-shaped layer at 256 tokens (blocks of 65-128 rows) the chain took
+// 0.75 us per stage whether or not the weights came from HBM, against the 0.64
+// us the weight stream needs.  So the general form runs EIGHT waves, two per
+// SIMD, as 4 (token tiles wm, wm + 4, ...) x 2 (halves of the weight rows): a
+// wave multiplies a quarter of the block's token tiles, and one wave's operand
+// reads overlap the other's matrix instructions.  Same ring, same operand
+// placement, same order of accumulation along the contraction (same bits).
+constexpr int kT8Waves = 8;
+constexpr int kT8Threads = kT8Waves * MOE_WAVE;
+constexpr int kT8Tok = 4;                 // token fetches per wave and stage, a full 256-row block
+constexpr int kT8Fetch = kT8Tok + 2;      // plus two weight fetches
+
+// Wave w issues the token fetches h = w + 8 q (q < 4) and the weight fetches
+// h = 32 + w + 8 q' (q' < 2) of the 48 per stage; fetch h is rows 8 (h & 1) .. of
+// block h / 2 and lands at stage base + h KiB.
+template <int MODE>
+__device__ __forceinline__ void tile8_rows(const FfnArgs& a, const TileItem& it, int lane, int wave,
+                                           int (&ids)[kT8Tok]) {
+#pragma unroll
+  for (int q = 0; q < kT8Tok; ++q) {
+    const int h = wave + kT8Waves * q, blk = h >> 1, u = h & 1;
+    const int p = min(it.r0 + blk * 16 + tile_fetch_row(lane, u), it.row_end - 1);
+    ids[q] = MODE == kGateUp ? a.perm[min(p, a.A - 1)] : 0;   // see tile_rows
+  }
+}
+
+template <int MODE>
+__device__ __forceinline__ void tile8_sources(const FfnArgs& a, const ExpertTable& tab,
+                                              const TileItem& it, const int (&ids)[kT8Tok], int lane,
+                                              int wave, const uint16_t* (&src)[kT8Fetch]) {
+  const int e = it.e;
+  const int n0 = it.slab * (MODE == kGateUp ? 64 : 128);
+  const int chunk = tile_fetch_chunk(lane);
+#pragma unroll
+  for (int q = 0; q < kT8Fetch; ++q) {
+    const int h = q < kT8Tok ? wave + kT8Waves * q : 32 + wave + kT8Waves * (q - kT8Tok);
+    const int blk = h >> 1, u = h & 1;
+    const int rr = tile_fetch_row(lane, u);   // row inside the 16-row block
+    if (q < kT8Tok) {
+      const int p = min(it.r0 + blk * 16 + rr, it.row_end - 1);   // bucket position
+      int row = p;                                                 // down: h is in bucket order
+      if (MODE == kGateUp) row = e >= a.E ? p - (a.A + (e - a.E) * a.T) : ids[q] / a.k;
+      src[q] = a.act + (size_t)row * a.K + chunk * 8;
+      continue;
+    }
+    const int j = blk - 16;
+    if (a.tiled) {
+      const uint16_t* W;
+      int n16;
+      if (MODE == kGateUp) {
+        W = static_cast<const uint16_t*>(j < 4 ? tab.Wg[e] : tab.Wu[e]);
+        n16 = n0 / 16 + (j & 3);
+      } else {
+        W = static_cast<const uint16_t*>(tab.Wd[e]);
+        n16 = n0 / 16 + j;
+      }
+      src[q] = W + weight_lane_offset(true, n16, a.K, lane) + (size_t)u * 512;
+    } else {
+      const uint16_t* rowp;
+      if (MODE == kGateUp) {
+        const uint16_t* W = static_cast<const uint16_t*>(j < 4 ? tab.Wg[e] : tab.Wu[e]);
+        rowp = W + (size_t)(n0 + (j & 3) * 16 + rr) * a.K;
+      } else {
+        rowp = static_cast<const uint16_t*>(tab.Wd[e]) + (size_t)(n0 + j * 16 + rr) * a.K;
+      }
+      src[q] = rowp + chunk * 8;
+    }
+  }
+  // pinned down here, not between the fetches (see tile_sources)
+#pragma unroll
+  for (int q = 0; q < kT8Fetch; ++q) asm volatile("" : "+v"(src[q]));
+}
+
+// This wave's fetches of stage st into ring buffer st % 3: the first NTOK of its
+// token fetches (token blocks 0 .. 4 NTOK - 1) and its two weight fetches.
+template <int NTOK>
+__device__ __forceinline__ void tile8_fetch(const uint16_t* const (&src)[kT8Fetch], int st, int w_adv,
+                                            int wave, unsigned char* ring) {
+  unsigned char* base = ring + (st % kTileStages) * kTileStage;
+#pragma unroll
+  for (int q = 0; q < kT8Fetch; ++q) {
+    if (q >= NTOK && q < kT8Tok) continue;
+    if (q >= kT8Tok)   // weights are read once: non-temporal (see tile_fetch)
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(src[q] + (size_t)st * w_adv),
+          (__attribute__((address_space(3))) void*)(base + (32 + wave + kT8Waves * (q - kT8Tok)) * kFragBytes),
+          16, 0, 2);
+    else
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(src[q] + (size_t)st * kTileK),
+          (__attribute__((address_space(3))) void*)(base + (wave + kT8Waves * q) * kFragBytes), 16, 0, 0);
+  }
+}
+
 // One item.  On entry the fetches of its stages 0 and 1 are in flight (issued
 // by the previous item, or by the kernel's preamble); before its own epilogue
 // it sets up the next item of this workgroup and issues that item's first two
 // stages, so the stores of one item and the cold first fetches of the next
 // overlap instead of adding up.
-// NJ = token tiles per wave that are multiplied (the block's tiles, taken
-// alternately by the two wave rows, rounded up): a compile-time bound, so the
-// accumulators stay in registers and a short block costs what it uses.
+// NJ = token tiles per wave that are multiplied (the block's tiles dealt to the
+// four wave rows, rounded up): a compile-time bound, so the accumulators stay
+// in registers and a short block costs what it uses.
 template <int MODE, int NJ>
 __device__ __forceinline__ void ffn_tile_block(const FfnArgs& a, const ExpertTable& tab,
                                                const TileItem& it, bool has_next,
                                                const TileItem& nxt,
-                                               const uint16_t* (&src)[kFetchPerWave],
+                                               const uint16_t* (&src)[kT8Fetch],
                                                unsigned char* ring) {
   const int r0 = it.r0, row_end = it.row_end;
-  const int lane = threadIdx.x & (MOE_WAVE - 1), wave = threadIdx.x / MOE_WAVE;
-  const int wm = wave & 1, wn = wave >> 1;
+  const int lane = threadIdx.x & (MOE_WAVE - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE);
+  const int wm = wave & 3, wn = wave >> 2;
   const int n0 = it.slab * (MODE == kGateUp ? 64 : 128);
   const int w_adv = a.tiled ? 1024 : kTileK;
   // where lane (r, g) finds row r, chunk 4 s + g of a block, for k-step s = 0, 1
@@ -648,41 +746,34 @@ __device__ __forceinline__ void ffn_tile_block(const FfnArgs& a, const ExpertTab
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks) rdw[ks] = a.tiled ? ks * kFragBytes + lane * 16 : rd[ks];
 
-  f32x4 acc[4][NJ];   // this wave's token tiles are wm, wm + 2, ...
+  f32x4 acc[4][NJ];   // this wave's token tiles are wm, wm + 4, ...
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < NJ; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  int next_ids[8];
+  int next_ids[kT8Tok];
 #pragma unroll
-  for (int q = 0; q < 8; ++q) next_ids[q] = 0;
+  for (int q = 0; q < kT8Tok; ++q) next_ids[q] = 0;
 
   const int ns = a.K / kTileK;
   for (int st = 0; st < ns; ++st) {
-    // this wave's fetches of stage st have landed once at most the fetches of
-    // the one younger stage already issued are still outstanding
-    // A bare barrier, not __syncthreads(): the fence that comes with the latter
-    // makes the compiler wait for EVERY outstanding fetch (the ones of the next
-    // stages too), which would put the whole ring one stage deep.  What the
-    // barrier has to order is covered by hand: the vmcnt wait above it (this
-    // wave's direct-to-LDS fetches of stage st have been written), and program
-    // order (a wave's LDS reads of stage st-1 fed MFMAs it has already issued).
-    // (Stages 2.. of an item fetch only the token blocks it multiplies, NJ + 4
-    // fetches per wave; the two stages an item inherits were fetched in full.
-    // Waiting for "all but the newest NJ + 4" is exact or conservative in both
-    // cases, because loads complete in order.)
-    if (st + 1 < ns) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(NJ + 4) : "memory");
+    // This wave's fetches of stage st have landed once at most the fetches of
+    // the one younger stage already issued are still outstanding (loads complete
+    // in order; NJ + 2 per wave and stage, six in the two stages an item
+    // inherits, so "all but the newest NJ + 2" is exact or conservative).  A
+    // bare barrier, not __syncthreads(): the fence that comes with the latter
+    // makes the compiler wait for EVERY outstanding fetch, which would put the
+    // whole ring one stage deep.  What the barrier has to order is covered by
+    // hand: the vmcnt wait above it (this wave's direct-to-LDS fetches of stage
+    // st have been written), and program order (a wave's LDS reads of stage
+    // st-1 fed MFMAs it has already issued).
+    if (st + 1 < ns) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(NJ + 2) : "memory");
     else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-    // the next item's row look-ups: issued early (ahead of this stage's fetches, so
-    // that the in-order wait above never has to wait for more than one stage of
-    // fetches), needed only after the last stage
-    if (st == 1 && has_next) tile_rows<MODE>(a, nxt, lane, wave, next_ids);
-    if (st + 2 < ns) tile_fetch<NJ>(src, st + 2, w_adv, wave, ring);   // into the buffer stage st-1 used
+    // the next item's row look-ups: issued early, needed only after the last stage
+    if (st == 1 && has_next) tile8_rows<MODE>(a, nxt, lane, wave, next_ids);
+    if (st + 2 < ns) tile8_fetch<NJ>(src, st + 2, w_adv, wave, ring);   // into the buffer stage st-1 used
     const unsigned char* base = ring + (st % kTileStages) * kTileStage;
-    // LDS reads of both k-steps are issued up front, in order; the MFMAs of the
-    // first k-step only wait for its own operands (LDS returns in order), so the
-    // second k-step's reads land while the matrix pipe is busy
     bf16x8 wf[2][4], tf[2][NJ];
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
@@ -695,7 +786,7 @@ __device__ __forceinline__ void ffn_tile_block(const FfnArgs& a, const ExpertTab
       }
 #pragma unroll
       for (int j = 0; j < NJ; ++j)
-        tf[ks][j] = *reinterpret_cast<const bf16x8*>(base + (wm + 2 * j) * kDblFrag + rd[ks]);
+        tf[ks][j] = *reinterpret_cast<const bf16x8*>(base + (wm + 4 * j) * kDblFrag + rd[ks]);
     }
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
@@ -704,15 +795,17 @@ __device__ __forceinline__ void ffn_tile_block(const FfnArgs& a, const ExpertTab
 #pragma unroll
         for (int i = 0; i < 4; ++i)
           acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ks][i], tf[ks][j], acc[i][j], 0, 0, 0);
-    // order for the scheduler: the first k-step's reads, then its MFMAs with the
-    // second k-step's reads slipped in one per two MFMAs, then the rest
-    __builtin_amdgcn_sched_group_barrier(0x100, 4 + NJ, 0);
+    if constexpr (NJ >= 2) {
+      // order for the scheduler: the first k-step's reads, then its MFMAs with the
+      // second k-step's reads slipped in one per two MFMAs, then the rest
+      __builtin_amdgcn_sched_group_barrier(0x100, 4 + NJ, 0);
 #pragma unroll
-    for (int q = 0; q < 4 + NJ; ++q) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      for (int q = 0; q < 4 + NJ; ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 8 * NJ - 2 * (4 + NJ), 0);
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, 8 * NJ - 2 * (4 + NJ), 0);
   }
 
   // D layout: lane holds rows 4*g .. 4*g+3 of the 16-row weight tile, column r = token
@@ -720,7 +813,7 @@ __device__ __forceinline__ void ffn_tile_block(const FfnArgs& a, const ExpertTab
     const int r = lane & 15, g = lane >> 4;
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
-      const int p = r0 + (wm + 2 * j) * 16 + r;
+      const int p = r0 + (wm + 4 * j) * 16 + r;
       if (p >= row_end) continue;
       if (MODE == kGateUp) {
         uint16_t* h = static_cast<uint16_t*>(a.out);
@@ -749,15 +842,15 @@ __device__ __forceinline__ void ffn_tile_block(const FfnArgs& a, const ExpertTab
   // epilogue is written out on both paths: behind the join of a conditional
   // the compiler would first wait for every outstanding fetch.)
   if (has_next) {
-    const uint16_t* next_src[kFetchPerWave];
-    if (ns < 2) tile_rows<MODE>(a, nxt, lane, wave, next_ids);
-    tile_sources<MODE, kFetchPerWave>(a, tab, nxt, next_ids, lane, wave, next_src);
+    const uint16_t* next_src[kT8Fetch];
+    if (ns < 2) tile8_rows<MODE>(a, nxt, lane, wave, next_ids);
+    tile8_sources<MODE>(a, tab, nxt, next_ids, lane, wave, next_src);
     asm volatile("s_barrier" ::: "memory");
-    tile_fetch<8>(next_src, 0, w_adv, wave, ring);   // in full: the next item's size is not a constant here
-    if (ns > 1) tile_fetch<8>(next_src, 1, w_adv, wave, ring);
+    tile8_fetch<kT8Tok>(next_src, 0, w_adv, wave, ring);   // in full: the next item's size is not a constant here
+    if (ns > 1) tile8_fetch<kT8Tok>(next_src, 1, w_adv, wave, ring);
     epilogue();
 #pragma unroll
-    for (int q = 0; q < kFetchPerWave; ++q) src[q] = next_src[q];
+    for (int q = 0; q < kT8Fetch; ++q) src[q] = next_src[q];
   } else {
     epilogue();
   }
@@ -840,8 +933,8 @@ __device__ __forceinline__ TileSplit tile_split(int count, int stride, bool allo
 // a row block's activations (and the row blocks that share a shared expert's
 // weights) are in flight together.
 template <int MODE>
-__global__ __launch_bounds__(kThreads, 1) void ffn_tile_kernel(FfnArgs a, ExpertTable tab,
-                                                               GroupList groups) {
+__global__ __launch_bounds__(kT8Threads, 1) void ffn_tile_kernel(FfnArgs a, ExpertTable tab,
+                                                                 GroupList groups) {
   extern __shared__ __attribute__((aligned(16))) unsigned char ring[];
   __shared__ TilePlan plan;
   tile_plan_build(plan, a, groups);
@@ -852,27 +945,28 @@ __global__ __launch_bounds__(kThreads, 1) void ffn_tile_kernel(FfnArgs a, Expert
   // round-robin only if allowed and the experts' blocks differ in size class
   const TileOrder order = tile_order(total, xcd, a.interleave && (plan.sizes & (plan.sizes - 1)) != 0);
   if (local >= order.count) return;
-  const int lane = threadIdx.x & (MOE_WAVE - 1), wave = threadIdx.x / MOE_WAVE;
+  const int lane = threadIdx.x & (MOE_WAVE - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE);
   const int w_adv = a.tiled ? 1024 : kTileK;
 
   TileItem it = tile_item(groups, plan, order.item(local), slabs);
-  const uint16_t* src[kFetchPerWave];
+  const uint16_t* src[kT8Fetch];
   {
-    int rows[8];
-    tile_rows<MODE>(a, it, lane, wave, rows);
-    tile_sources<MODE, kFetchPerWave>(a, tab, it, rows, lane, wave, src);
-    tile_fetch<8>(src, 0, w_adv, wave, ring);
-    if (a.K / kTileK > 1) tile_fetch<8>(src, 1, w_adv, wave, ring);
+    int rows[kT8Tok];
+    tile8_rows<MODE>(a, it, lane, wave, rows);
+    tile8_sources<MODE>(a, tab, it, rows, lane, wave, src);
+    tile8_fetch<kT8Tok>(src, 0, w_adv, wave, ring);
+    if (a.K / kTileK > 1) tile8_fetch<kT8Tok>(src, 1, w_adv, wave, ring);
   }
   while (true) {
     const bool has_next = local + stride < order.count;
     TileItem nxt = it;
     if (has_next) nxt = tile_item(groups, plan, order.item(local + stride), slabs);
     const int tiles = (min(it.row_end - it.r0, kTileRows) + 15) / 16;
-    if (tiles <= 4) ffn_tile_block<MODE, 2>(a, tab, it, has_next, nxt, src, ring);
-    else if (tiles <= 8) ffn_tile_block<MODE, 4>(a, tab, it, has_next, nxt, src, ring);
-    else if (tiles <= 12) ffn_tile_block<MODE, 6>(a, tab, it, has_next, nxt, src, ring);
-    else ffn_tile_block<MODE, 8>(a, tab, it, has_next, nxt, src, ring);
+    if (tiles <= 4) ffn_tile_block<MODE, 1>(a, tab, it, has_next, nxt, src, ring);
+    else if (tiles <= 8) ffn_tile_block<MODE, 2>(a, tab, it, has_next, nxt, src, ring);
+    else if (tiles <= 12) ffn_tile_block<MODE, 3>(a, tab, it, has_next, nxt, src, ring);
+    else ffn_tile_block<MODE, 4>(a, tab, it, has_next, nxt, src, ring);
     if (!has_next) break;
     it = nxt;
     local += stride;
@@ -1232,9 +1326,12 @@ static_assert(2 * kWideTiles % kWideWaves == 0, "token fetches must divide over 
 // of loads that are younger than the tokens of the stage with d remaining:
 // those of the two stages before it.
 constexpr int wide_issue_w(int d) { return d > kWideWLead ? 4 : 0; }
-constexpr int wide_issue_t(int d) { return d > kWideTLead ? kWideFetch : 0; }
-constexpr int wide_wait(int d) {
-  return wide_issue_w(d + 2) + wide_issue_t(d + 2) + wide_issue_w(d + 1) + wide_issue_t(d + 1);
+// (ntok = token fetches a stage of this item issues per wave: only the blocks it
+// multiplies.  The stages an item inherits were fetched in full, which makes the
+// first waits conservative, never short.)
+constexpr int wide_issue_t(int d, int ntok) { return d > kWideTLead ? ntok : 0; }
+constexpr int wide_wait(int d, int ntok) {
+  return wide_issue_w(d + 2) + wide_issue_t(d + 2, ntok) + wide_issue_w(d + 1) + wide_issue_t(d + 1, ntok);
 }
 
 // The token fetches of this form go through a buffer resource (base = the
@@ -1283,11 +1380,12 @@ __device__ __forceinline__ void wide_offsets(const FfnArgs& a, const TileItem& i
 }
 
 // Token fetches of stage st into ring slot st mod 4.
+template <int NTOK = kWideFetch>
 __device__ __forceinline__ void wide_fetch(ActRsrc rsrc, const uint32_t (&off)[kWideFetch], int st,
                                            int wave, unsigned char* ring) {
   unsigned char* base = ring + (st % kWideStages) * kWideStage;
 #pragma unroll
-  for (int q = 0; q < kWideFetch; ++q)
+  for (int q = 0; q < NTOK; ++q)
     __builtin_amdgcn_raw_ptr_buffer_load_lds(
         rsrc,
         (__attribute__((address_space(3))) void*)(base + (wave + kWideWaves * q) * kFragBytes), 16,
@@ -1371,8 +1469,10 @@ __device__ __forceinline__ void ffn_wide_block(const FfnArgs& a, const ExpertTab
   auto stage = [&](int st, auto set_tag, auto remaining_tag, auto rows_tag) {
     constexpr int SET = decltype(set_tag)::value;
     constexpr int D = decltype(remaining_tag)::value;
-    constexpr bool IW = wide_issue_w(D) > 0, IT = wide_issue_t(D) > 0;
-    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(wide_wait(D)) : "memory");
+    // token blocks this item multiplies: 2 NT fetches of the 32, NT / 4 per wave
+    constexpr int NTOK = NT / 4;
+    constexpr bool IW = wide_issue_w(D) > 0, IT = wide_issue_t(D, NTOK) > 0;
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(wide_wait(D, NTOK)) : "memory");
     if (decltype(rows_tag)::value && has_next) {
       // the lane index re-derived and made opaque here: the look-up addresses are
       // then worked out on the spot instead of ahead of the item (where they would
@@ -1382,7 +1482,7 @@ __device__ __forceinline__ void ffn_wide_block(const FfnArgs& a, const ExpertTab
       wide_rows<MODE>(a, nxt, lane_here, wave, next_ids);
     }
     if (IW) load_w(Tag<(SET + kWideWLead) % WS>{}, st + kWideWLead);
-    if (IT) wide_fetch(rsrc, src, st + kWideTLead, wave, ring);
+    if (IT) wide_fetch<NTOK>(rsrc, src, st + kWideTLead, wave, ring);
     const unsigned char* base = ring + (st % kWideStages) * kWideStage;
     bf16x8 tf[2][NT];
 #pragma unroll
@@ -1400,7 +1500,7 @@ __device__ __forceinline__ void ffn_wide_block(const FfnArgs& a, const ExpertTab
     // order for the scheduler: the loads, some LDS reads ahead, then one more
     // read per two MFMAs
     constexpr int AHEAD = 6;
-    if (IW || IT) __builtin_amdgcn_sched_group_barrier(0x020, (IW ? 4 : 0) + (IT ? kWideFetch : 0), 0);
+    if (IW || IT) __builtin_amdgcn_sched_group_barrier(0x020, (IW ? 4 : 0) + (IT ? NTOK : 0), 0);
     __builtin_amdgcn_sched_group_barrier(0x100, AHEAD, 0);
 #pragma unroll
     for (int q = 0; q < 2 * NT - AHEAD; ++q) {
@@ -1649,7 +1749,7 @@ moe_status launch_tile(const moe_shape& s, const FfnArgs& args, const ExpertTabl
       hipLaunchKernelGGL((ffn_tile_small_kernel<MODE>), dim3(grid), dim3(kThreads), kTileLds, stream,
                          args, tab, groups);
     else
-      hipLaunchKernelGGL((ffn_tile_kernel<MODE>), dim3(grid), dim3(kThreads), kTileLds, stream, args,
+      hipLaunchKernelGGL((ffn_tile_kernel<MODE>), dim3(grid), dim3(kT8Threads), kTileLds, stream, args,
                          tab, groups);
   }
   MOE_HIP(hipGetLastError());
