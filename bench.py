@@ -366,7 +366,7 @@ def traffic_from_profiles(kernel, workload, T, layout, lib):
             kv = dict(tok.split("=", 1) for tok in line.split()[1:] if "=" in tok)
             if (kv.get("kernel") == kernel and kv.get("workload") == workload
                     and kv.get("tokens") == str(T) and kv.get("layout") == layout
-                    and kv.get("lib", "").replace("_", " ") == lib):
+                    and kv.get("lib") == lib.replace(" ", "_")):
                 return {"bytes": int(kv["total"]), "source": os.path.relpath(path, ROOT)}
     return None
 
