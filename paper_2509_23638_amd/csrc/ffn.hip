@@ -1734,7 +1734,9 @@ moe_status launch_tile(const moe_shape& s, const FfnArgs& args, const ExpertTabl
   const int slabs = wide ? (MODE == kGateUp ? s.F / kWideSlabGateUp : s.H / kWideSlabDown)
                          : (MODE == kGateUp ? s.F / 64 : s.H / 128);
   // one persistent workgroup per compute unit, never more than there can be items
-  const int block_rows = wide ? kWideRows : (s.T <= kSmallRows ? kSmallRows : kTileRows);
+  static const char* small_env = tune_env("MOE_TUNE_SMALL");   // 0: the general kernel for small launches too
+  const bool small = s.T <= kSmallRows && !(small_env && small_env[0] == '0');
+  const int block_rows = wide ? kWideRows : (small ? kSmallRows : kTileRows);
   const int grid = (std::min(slabs * max_row_blocks(s, block_rows), n_cu) + 7) / 8 * 8;
   if (wide) {
     // rows of the activation matrix: tokens for gate/up, bucket rows for down
@@ -1745,7 +1747,7 @@ moe_status launch_tile(const moe_shape& s, const FfnArgs& args, const ExpertTabl
     MOE_HIP(hipLaunchKernel(WideKernels<MODE>::get(r), dim3(grid), dim3(kWideThreads), params,
                             kWideLds, stream));
   } else {
-    if (s.T <= kSmallRows)   // every bucket, a shared expert's too, has at most T rows
+    if (small)   // every bucket, a shared expert's too, has at most T rows
       hipLaunchKernelGGL((ffn_tile_small_kernel<MODE>), dim3(grid), dim3(kThreads), kTileLds, stream,
                          args, tab, groups);
     else
@@ -1764,7 +1766,7 @@ moe_status launch_tile(const moe_shape& s, const FfnArgs& args, const ExpertTabl
 // another wave's activations, so the B fragments go from global memory (h is a
 // few MB and lives in L2) straight to registers: no LDS and no barrier in the
 // loop.  The four partial accumulators meet in LDS once, summed in wave order.
-template <int NT, bool ONCE>
+template <int NT, bool ONCE, int NW>
 struct SplitKStreamer {
   const uint16_t* w0;
   const uint16_t* w1;
@@ -1789,7 +1791,7 @@ struct SplitKStreamer {
 #pragma unroll
     for (int s = 0; s < kStepsPerChunk; ++s) {
       wreg[SET][s][0] = load_weight(w0 + (size_t)(c * kStepsPerChunk + s) * wstep);
-      wreg[SET][s][1] = load_weight(w1 + (size_t)(c * kStepsPerChunk + s) * wstep);
+      if (NW == 2) wreg[SET][s][1] = load_weight(w1 + (size_t)(c * kStepsPerChunk + s) * wstep);
     }
   }
 
@@ -1800,7 +1802,8 @@ struct SplitKStreamer {
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
         acc0[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[SET][s][0], breg[SET][t][s], acc0[t], 0, 0, 0);
-        acc1[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[SET][s][1], breg[SET][t][s], acc1[t], 0, 0, 0);
+        if (NW == 2)
+          acc1[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[SET][s][1], breg[SET][t][s], acc1[t], 0, 0, 0);
       }
   }
 
@@ -1823,18 +1826,19 @@ struct SplitKStreamer {
   }
 };
 
-constexpr int kSplitRows = 32;   // weight rows per workgroup
+constexpr int kSplitRows = 32;   // weight rows per workgroup (16 in the one-tile form)
 constexpr int kSplitTok = 32;    // bucket rows per pass (NT <= 2)
+constexpr int kSplitOneTileIds = 16;  // up to this many (token, slot) pairs: the one-tile form
 
-template <int NT, bool ONCE>
+template <int NT, bool ONCE, int NW>
 __device__ __forceinline__ void down_splitk_block(const FfnArgs& a, const uint16_t* Wd, int n0,
                                                   int r0, int row_end, float* red) {
   const int lane = threadIdx.x & (MOE_WAVE - 1), wave = threadIdx.x / MOE_WAVE;
   const int r = lane & 15, g = lane >> 4;
-  SplitKStreamer<NT, ONCE> st;
+  SplitKStreamer<NT, ONCE, NW> st;
   st.wstep = weight_kstep_stride(a.tiled);
   st.w0 = Wd + weight_lane_offset(a.tiled, n0 / 16, a.K, lane);
-  st.w1 = Wd + weight_lane_offset(a.tiled, n0 / 16 + 1, a.K, lane);
+  st.w1 = Wd + weight_lane_offset(a.tiled, n0 / 16 + (NW - 1), a.K, lane);
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
     const int p = min(r0 + t * 16 + r, row_end - 1);
@@ -1848,12 +1852,13 @@ __device__ __forceinline__ void down_splitk_block(const FfnArgs& a, const uint16
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
     reinterpret_cast<f32x4*>(red)[((wave * NT + t) * 2 + 0) * MOE_WAVE + lane] = st.acc0[t];
-    reinterpret_cast<f32x4*>(red)[((wave * NT + t) * 2 + 1) * MOE_WAVE + lane] = st.acc1[t];
+    if (NW == 2) reinterpret_cast<f32x4*>(red)[((wave * NT + t) * 2 + 1) * MOE_WAVE + lane] = st.acc1[t];
   }
   __syncthreads();
   float* y = static_cast<float*>(a.out);
   for (int q = wave; q < NT * 2; q += kWaves) {  // q = t * 2 + tile
     const int t = q >> 1, tile = q & 1;
+    if (tile >= NW) continue;
     f32x4 sum = reinterpret_cast<const f32x4*>(red)[((0 * NT + t) * 2 + tile) * MOE_WAVE + lane];
 #pragma unroll
     for (int w = 1; w < kWaves; ++w) {
@@ -1867,6 +1872,11 @@ __device__ __forceinline__ void down_splitk_block(const FfnArgs& a, const uint16
   }
 }
 
+// NW = weight tiles per wave: 2 (32 rows per workgroup), or 1 (16 rows) for the
+// very smallest batches, where at most a handful of experts is active and twice
+// the workgroups put twice the loads in flight.  A row's sum is the same four
+// quarter sums in the same order either way.
+template <int NW>
 __global__ __launch_bounds__(kThreads) void ffn_down_splitk_kernel(FfnArgs a, ExpertTable tab,
                                                                    GroupList groups) {
   __shared__ __attribute__((aligned(16))) float red[kWaves * 2 * 2 * MOE_WAVE * 4];  // 16 KiB
@@ -1882,14 +1892,14 @@ __global__ __launch_bounds__(kThreads) void ffn_down_splitk_kernel(FfnArgs a, Ex
   const int r0 = row_begin + blockIdx.z * kSplitTok;
   if (r0 >= row_end) return;
   const uint16_t* Wd = static_cast<const uint16_t*>(tab.Wd[e]);
-  const int n0 = blockIdx.x * kSplitRows;
+  const int n0 = blockIdx.x * (16 * NW);
   const bool once = blockIdx.z == 0 && row_end - r0 <= kSplitTok;   // the bucket's only pass
   if (row_end - r0 <= 16) {
-    if (once) down_splitk_block<1, true>(a, Wd, n0, r0, row_end, red);
-    else down_splitk_block<1, false>(a, Wd, n0, r0, row_end, red);
+    if (once) down_splitk_block<1, true, NW>(a, Wd, n0, r0, row_end, red);
+    else down_splitk_block<1, false, NW>(a, Wd, n0, r0, row_end, red);
   } else {
-    if (once) down_splitk_block<2, true>(a, Wd, n0, r0, row_end, red);
-    else down_splitk_block<2, false>(a, Wd, n0, r0, row_end, red);
+    if (once) down_splitk_block<2, true, NW>(a, Wd, n0, r0, row_end, red);
+    else down_splitk_block<2, false, NW>(a, Wd, n0, r0, row_end, red);
   }
 }
 
@@ -2092,8 +2102,14 @@ moe_status launch_ffn_down(const moe_shape& s, const FfnScratch& scratch, const 
                          dim3(kThreads), 0, stream, dn, tab, groups);
     } else if (v == kSplitK) {
       const int tok_blocks = (s.T + kSplitTok - 1) / kSplitTok;
-      hipLaunchKernelGGL(ffn_down_splitk_kernel, dim3(s.H / kSplitRows, groups.n, tok_blocks),
-                         dim3(kThreads), 0, stream, dn, tab, groups);
+      static const char* nw_env = tune_env("MOE_TUNE_SPLITNW");
+      const bool one_tile = nw_env ? nw_env[0] == '1' : (long)s.T * s.k <= kSplitOneTileIds;
+      if (one_tile)
+        hipLaunchKernelGGL(ffn_down_splitk_kernel<1>, dim3(s.H / 16, groups.n, tok_blocks),
+                           dim3(kThreads), 0, stream, dn, tab, groups);
+      else
+        hipLaunchKernelGGL(ffn_down_splitk_kernel<2>, dim3(s.H / kSplitRows, groups.n, tok_blocks),
+                           dim3(kThreads), 0, stream, dn, tab, groups);
     } else if (v != kStream64) {
       hipLaunchKernelGGL((ffn_stream_kernel<kDown, 8, 1>), dim3(s.H / (kWaves * 32), groups.n, (s.T + 127) / 128),
                          dim3(kThreads), 0, stream, dn, tab, groups);
