@@ -13,7 +13,8 @@ already in HBM (mean over the K timed steps; `ms_per_step_median` comes from
 a second, untimed pass with one event pair per step).  `roofline` prices the
 dominant kernel (gate/up weight stream) against the 8 TB/s HBM peak using its
 algorithmic bytes and its average duration measured with HIP events recorded
-between the kernels inside the timed region; `roofline.layer` prices the whole
+between the kernels inside the timed region (on every fourth step: an event
+pair costs its step about 5 us); `roofline.layer` prices the whole
 layer step the same way; `roofline.traffic` is read from the committed counter
 summaries under profiles/ and is null unless one was measured on this very
 kernel, workload and library version.  `cpu_baseline` times the fp64 CPU
@@ -433,9 +434,10 @@ def run_layer(args, torch, B, workload, T, steps, warmup, weight_sets, headline)
         B.moe_layer_forward(ctx, sh, layers[i % len(layers)], X, out, ws)
     torch.cuda.synchronize()
 
-    # the timed region: K layer steps, with two HIP event markers per step around
-    # the dominant kernel (gate/up) recorded on the kernels' own stream
-    ctx.phase_timing(2)
+    # the timed region: K layer steps; on every fourth of them two HIP event markers
+    # around the dominant kernel (gate/up), recorded on the kernels' own stream (a
+    # pair costs about 5 us of the step it is in)
+    ctx.phase_timing(3)
     ctx.phase_times(reset=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -464,7 +466,8 @@ def run_layer(args, torch, B, workload, T, steps, warmup, weight_sets, headline)
 
     ms_per_step = dt / steps * 1e3
     used = [n_active[i % len(layers)] for i in range(steps)]
-    gu_bytes = float(np.mean([gate_up_bytes(n) for n in used]))
+    # the marked launches are those of steps 0, 4, 8, ...: their bytes
+    gu_bytes = float(np.mean([gate_up_bytes(n) for n in used[::4]]))
     all_bytes = float(np.mean([layer_bytes(n) for n in used]))
     flops = 6.0 * rows * cfg.H * cfg.F
     gu_ms = ph2["gate_up_only_ms"] / max(1, ph2["gate_up_only_layers"])
@@ -480,7 +483,8 @@ def run_layer(args, torch, B, workload, T, steps, warmup, weight_sets, headline)
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": tr["bytes"] if tr else None,
                      "traffic_source": tr["source"] if tr else None,
-                     "kernel": kernel, "kernel_ms": gu_ms, "algorithmic_bytes": gu_bytes,
+                     "kernel": kernel, "kernel_ms": gu_ms, "kernel_launches_timed": int(ph2["gate_up_only_layers"]),
+                     "algorithmic_bytes": gu_bytes,
                      "layer": {"algorithmic_bytes": all_bytes,
                                "achieved": all_bytes / (ms_per_step * 1e-3) / 1e9,
                                "frac": all_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,

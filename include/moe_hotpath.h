@@ -312,11 +312,14 @@ moe_status moe_set_option(moe_ctx* ctx, int32_t option, int64_t value);
  *           and after each of the five kernels (route, permute, gate/up, down,
  *           combine): six markers per layer;
  *   mode 2: only the two markers around the gate/up kernel (the dominant one),
- *           which perturbs the layer's own timing the least;
+ *           which perturbs the layer's own timing less (about 5 us per layer);
+ *   mode 3: as mode 2, on every fourth call only (the first after the mode was
+ *           set, then every fourth): a sample of the launches of a timed
+ *           region at a quarter of the cost;
  *   mode 0: off.
  * moe_phase_times_get waits for the recorded layers and returns the summed
  * durations: the five phases over `n_layers` mode-1 layers, and
- * `gate_up_only_ms` over `gate_up_only_layers` mode-2 layers. */
+ * `gate_up_only_ms` over `gate_up_only_layers` layers marked in mode 2 or 3. */
 typedef struct {
   double route_ms, permute_ms, gate_up_ms, down_ms, combine_ms;
   int64_t n_layers;

@@ -71,7 +71,8 @@ struct moe_ctx {
   int copy_split = 1;        // 1: one copy per expert when its matrices are contiguous on the
                              // host; 3: one copy per matrix, first phase gated on gate+up only
   // optional per-phase timing of all-resident layers (6 boundary events each)
-  int phase_timing = 0;      // 0 off, 1 all five phases, 2 only the gate/up phase
+  int phase_timing = 0;      // 0 off, 1 all five phases, 2 only the gate/up phase, 3 = 2 on every fourth call
+  int phase_calls = 0;       // calls since the mode was set (mode 3 samples by it)
   std::vector<hipEvent_t> phase_events;  // 6 (or 2) per timed layer, in call order
   std::vector<int> phase_kinds;          // per timed layer: 1 or 2
   std::vector<hipEvent_t> phase_free;
@@ -365,7 +366,8 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
                   "moe_layer_forward: non-resident expert %d has no pinned host copy", e);
   }
 
-  const int timed = all_resident ? c->phase_timing : 0;
+  int timed = all_resident ? c->phase_timing : 0;
+  if (timed == 3) timed = (c->phase_calls++ & 3) == 0 ? 2 : 0;
   // mark i of the six phase boundaries; mode 2 records only the two around gate/up
 #define PHASE_MARK(i)                                            \
   do {                                                           \
@@ -698,8 +700,9 @@ extern "C" moe_status moe_set_option(moe_ctx* c, int32_t option, int64_t value) 
 
 extern "C" moe_status moe_phase_timing(moe_ctx* c, int32_t mode) {
   MOE_REQUIRE(c, "moe_phase_timing: NULL context");
-  MOE_REQUIRE(mode >= 0 && mode <= 2, "moe_phase_timing: mode must be 0, 1 or 2");
+  MOE_REQUIRE(mode >= 0 && mode <= 3, "moe_phase_timing: mode must be 0, 1, 2 or 3");
   c->phase_timing = mode;
+  c->phase_calls = 0;
   return MOE_OK;
 }
 
