@@ -806,3 +806,39 @@ def test_repeated_forwards_are_bit_identical(B, name):
             assert torch.equal(out.view(torch.int16), first.view(torch.int16))
     ctx.close()
 
+
+
+def test_phase_markers_count_the_layers_they_mark_and_leave_results_alone(B):
+    """The measurement markers (all phases, gate/up only, gate/up on every fourth
+    call) report the number of layers they marked and never change an output bit."""
+    cfg = SMALL[1]
+    L = make_layer(cfg)
+    sh = _shape(B, cfg, L["X"].shape[0])
+    ctx = B.Context(sh)
+    Wg, Wu, Wd = _experts_dev(B, L, "row_major")
+    layer = B.make_layer_desc(sh, to_dev(L["Wr"]), to_dev(L["b"]), dev=(Wg, Wu, Wd))
+    X = to_dev(L["X"])
+    ws = B.alloc_workspace(sh)
+    outs = {}
+    for mode, calls in ((0, 1), (1, 3), (2, 5), (3, 9)):
+        out = torch.empty_like(X)
+        ctx.phase_timing(mode)
+        ctx.phase_times(reset=True)
+        for _ in range(calls):
+            B.moe_layer_forward(ctx, sh, layer, X, out, ws)
+        torch.cuda.synchronize()
+        t = ctx.phase_times(reset=True)
+        outs[mode] = to_host_bits(out)
+        want_all = calls if mode == 1 else 0
+        want_gu = {0: 0, 1: 0, 2: calls, 3: (calls + 3) // 4}[mode]
+        assert t["n_layers"] == want_all and t["gate_up_only_layers"] == want_gu, (mode, t)
+        if want_all:
+            assert min(t[k] for k in ("route_ms", "permute_ms", "gate_up_ms", "down_ms", "combine_ms")) > 0
+        if want_gu:
+            assert t["gate_up_only_ms"] > 0
+    ctx.phase_timing(0)
+    with pytest.raises(B.MoEError):
+        ctx.phase_timing(4)
+    for mode in (1, 2, 3):
+        assert np.array_equal(outs[mode], outs[0])
+    ctx.close()
