@@ -249,7 +249,7 @@ def run_c5(args, torch, B):
                     costs.r_hit = agg["n_hit"] / agg["n_prefetch_issued"]
                 pol = {"gate_top2": "gate_topn", "presched": "presched", "none": "none"}[args.c5_policy]
                 x, st = stack.step_online(Xs[s], pol, costs=costs, n_prefetch=NPF,
-                                          wrap_prefetch=False)
+                                          wrap_prefetch=False, want_stats=want_stats)
             for d in st:
                 for k_ in agg:
                     agg[k_] += d[k_]
@@ -279,11 +279,11 @@ def run_c5(args, torch, B):
     costs.t_g = t_layer / E
     costs.t_attn = t_layer          # the only time per layer the link has no on-demand work
     # hit / miss accounting from an untimed pass with stats; the timed passes run without
-    # (the fixed-mask policy then needs no host wait where everything was prefetched; the
-    # online policies read predicted counts back every layer either way)
+    # (a layer whose non-resident experts were all prefetched then needs no host wait; the
+    # online policies wait for their prediction only after the layer has been queued)
     _, (agg, same0) = timed(run_streamed)
     stack.ctx.stream_totals(reset=True)
-    fast = args.c5_policy == "noisy_top2"
+    fast = True
     earlier = []
     for rep in range(args.c5_repeat):
         t_wall, (agg_t, same) = timed(lambda: run_streamed(want_stats=not fast))

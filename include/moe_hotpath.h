@@ -253,6 +253,32 @@ moe_status moe_layer_forward(moe_ctx* ctx, const moe_shape* shape,
                              void* workspace, void* stream,
                              moe_layer_stats* stats);
 
+/* The prefetch step of moe_layer_forward as a call of its own, for a scheduler
+ * that decides the prefetch set while the current layer is already queued
+ * (Section 4.3: the decision for layer l+1 uses what layer l's gate has just
+ * activated; Section 4.4: prefetches run on the side stream behind the
+ * on-demand loads).  Call it after the moe_layer_forward of layer l (given no
+ * prefetch mask) and before that of layer l+1: it queues the copies of
+ * `next_layer`'s experts named in host_prefetch_mask (HOST words, ceil(E/64);
+ * ascending expert order, as many as a prefetch group has slots) into the
+ * group the next moe_layer_forward call reads, behind every copy queued so
+ * far, and drops what that group held.  Never blocks on the GPU.
+ *   *n_issued (may be NULL) receives the number of copies queued.
+ * Errors: NULL argument, expert without a pinned copy, expert larger than the
+ * context's slots. */
+moe_status moe_prefetch(moe_ctx* ctx, const moe_shape* shape, const moe_layer_desc* next_layer,
+                        const uint64_t* host_prefetch_mask, void* stream, int32_t* n_issued);
+
+/* The per-expert token counts of the layer the last moe_layer_forward call
+ * ran (the pending tokens per expert of Section 4.3.2, Premise 1), for a
+ * scheduler on the host.  Needs MOE_OPT_EXPORT_COUNTS: every layer call then
+ * queues a copy of its E counts to pinned host memory right behind the
+ * bucketing kernel and goes on without waiting; this call waits for that copy
+ * (the layer's routing and bucketing, not its FFN) and hands the counts over.
+ *   host_count [E] int32, E = the shape's routed experts.
+ * Errors: option not set / no layer run yet, E differs from the last layer's. */
+moe_status moe_layer_counts(moe_ctx* ctx, int32_t* host_count, int32_t E);
+
 /* ---- the block, for callers that cannot allocate ---------------------------
  * For code under HIP graph capture, tight serving loops and harnesses that
  * forbid hipMalloc: the same block as moe_layer_forward for a layer whose
@@ -302,8 +328,10 @@ moe_status moe_stream_totals_get(moe_ctx* ctx, moe_stream_totals* out, int32_t r
  *   contiguous in pinned host memory (Wu = Wg + H*F elements, Wd = Wu + H*F)
  *   moves as one copy; 3 = one copy per matrix in need order (gate, up, down)
  *   with the first FFN phase gated on gate+up only (Section 4.4's sub-tensor
- *   granularity).  Non-contiguous experts always move as three copies. */
-typedef enum { MOE_OPT_SYNC_COPIES = 0, MOE_OPT_COPY_SPLIT = 1 } moe_option;
+ *   granularity).  Non-contiguous experts always move as three copies.
+ * MOE_OPT_EXPORT_COUNTS (default 0): non-zero = every moe_layer_forward call
+ *   also copies its per-expert token counts to the host (see moe_layer_counts). */
+typedef enum { MOE_OPT_SYNC_COPIES = 0, MOE_OPT_COPY_SPLIT = 1, MOE_OPT_EXPORT_COUNTS = 2 } moe_option;
 moe_status moe_set_option(moe_ctx* ctx, int32_t option, int64_t value);
 
 /* Optional per-phase timing of layers whose experts are all resident, for

@@ -18,7 +18,7 @@ from .build import LIB
 
 MOE_F32, MOE_BF16 = 0, 1
 MOE_ROW_MAJOR, MOE_TILED = 0, 1
-MOE_OPT_SYNC_COPIES, MOE_OPT_COPY_SPLIT = 0, 1
+MOE_OPT_SYNC_COPIES, MOE_OPT_COPY_SPLIT, MOE_OPT_EXPORT_COUNTS = 0, 1, 2
 STATUS = {0: "MOE_OK", -1: "MOE_ERR_INVALID_ARG", -2: "MOE_ERR_UNSUPPORTED",
           -3: "MOE_ERR_WORKSPACE", -4: "MOE_ERR_HIP", -5: "MOE_ERR_SLOT_EXHAUSTED"}
 
@@ -115,6 +115,9 @@ _lib.moe_layer_forward.argtypes = [_P, _SH, C.POINTER(moe_layer_desc), C.POINTER
                                    C.POINTER(moe_layer_desc), C.POINTER(C.c_uint64),
                                    _P, _P, _P, _P, _P, C.POINTER(moe_layer_stats)]
 _lib.moe_layer_forward_static.argtypes = [_SH, C.POINTER(moe_layer_desc), _P, _P, _P, _P]
+_lib.moe_prefetch.argtypes = [_P, _SH, C.POINTER(moe_layer_desc), C.POINTER(C.c_uint64), _P,
+                              C.POINTER(C.c_int32)]
+_lib.moe_layer_counts.argtypes = [_P, C.POINTER(C.c_int32), C.c_int32]
 _lib.moe_static_workspace_bytes.restype = C.c_size_t
 _lib.moe_static_workspace_bytes.argtypes = []
 _lib.moe_stream_totals_get.argtypes = [_P, C.POINTER(moe_stream_totals), C.c_int32]
@@ -141,7 +144,8 @@ for _n in ("moe_counter_add", "moe_hot_table", "moe_predict_counts", "moe_presch
            "moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_create",
            "moe_destroy", "moe_layer_forward", "moe_layer_forward_static", "moe_stream_totals_get",
            "moe_workspace_views", "moe_phase_timing", "moe_phase_times_get", "moe_probe_copy", "moe_probe_read",
-           "moe_probe_read_nt", "moe_rmsnorm", "moe_set_option", "moe_pack_weights"):
+           "moe_probe_read_nt", "moe_rmsnorm", "moe_set_option", "moe_pack_weights", "moe_prefetch",
+           "moe_layer_counts"):
     getattr(_lib, _n).restype = C.c_int32
 
 EXPORTS = ["moe_version", "moe_last_error", "moe_workspace_bytes", "moe_route", "moe_permute",
@@ -151,7 +155,7 @@ EXPORTS = ["moe_version", "moe_last_error", "moe_workspace_bytes", "moe_route", 
            "moe_rmsnorm", "moe_set_option", "moe_pack_weights",
            "moe_counter_add", "moe_hot_table", "moe_predict_counts", "moe_presched",
            "moe_ffn_kernel_name", "moe_layer_forward_static", "moe_static_workspace_bytes",
-           "moe_pending_experts", "moe_prefetch_hottest"]
+           "moe_pending_experts", "moe_prefetch_hottest", "moe_prefetch", "moe_layer_counts"]
 
 
 def _check(st: int):
@@ -318,6 +322,16 @@ class Context:
     def set_sync_copies(self, enable: bool):
         _check(_lib.moe_set_option(self._h, MOE_OPT_SYNC_COPIES, 1 if enable else 0))
 
+    def set_export_counts(self, enable: bool):
+        _check(_lib.moe_set_option(self._h, MOE_OPT_EXPORT_COUNTS, 1 if enable else 0))
+
+    def layer_counts(self, E: int):
+        """Token counts per expert of the layer the last moe_layer_forward ran."""
+        import numpy as np
+        out = (C.c_int32 * E)()
+        _check(_lib.moe_layer_counts(self._h, out, E))
+        return np.frombuffer(out, dtype=np.int32).copy()
+
     def set_copy_split(self, n: int):
         _check(_lib.moe_set_option(self._h, MOE_OPT_COPY_SPLIT, n))
 
@@ -381,6 +395,14 @@ def moe_layer_forward(ctx: Context, shape, layer: Layer, X, out, workspace, resi
         _ptr(workspace, "workspace", (torch.uint8,), moe_workspace_bytes(shape)),
         _stream(stream), C.byref(stats) if stats is not None else None))
     return stats.as_dict() if stats is not None else None
+
+
+def moe_prefetch(ctx: Context, shape, next_layer: Layer, prefetch_mask, stream=None) -> int:
+    """The prefetch step as a call of its own; returns the number of copies queued."""
+    n = C.c_int32(0)
+    _check(_lib.moe_prefetch(ctx._h, C.byref(shape), C.byref(next_layer.desc),
+                             _mask_words(prefetch_mask, shape.E), _stream(stream), C.byref(n)))
+    return n.value
 
 
 def moe_static_workspace_bytes() -> int:

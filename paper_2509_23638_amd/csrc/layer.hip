@@ -61,6 +61,11 @@ struct moe_ctx {
   hipStream_t copy_stream = nullptr;
   hipEvent_t ev_counts = nullptr;
   int32_t* host_counts = nullptr;  // pinned, MOE_MAX_E ints
+  // MOE_OPT_EXPORT_COUNTS: every layer call also leaves its per-expert token counts here
+  bool export_counts = false;
+  int32_t* export_host = nullptr;  // pinned, MOE_MAX_E ints
+  hipEvent_t ev_export = nullptr;
+  int export_n = 0;                // experts of the last exported layer (0: none yet)
   std::vector<moe::CopyRec> pending;   // queued copies in stream order, oldest first
   hipEvent_t held_done = nullptr;      // `done` of the newest harvested copy (the next
                                        // record may start its interval there)
@@ -231,6 +236,27 @@ moe_status phase_event(moe_ctx* c, hipStream_t stream) {
 
 inline bool bit(const uint64_t* m, int e) { return (m[e >> 6] >> (e & 63)) & 1ull; }
 
+// Queue the copies of `layer`'s experts named in `mask` into the slots of one
+// prefetch group (as many as it has), in ascending expert order.  Whatever the
+// group held before is dropped.
+moe_status issue_prefetch(moe_ctx* c, const moe_shape& s, std::vector<Slot>& group,
+                          const moe_layer_desc* layer, const uint64_t* mask, hipStream_t stream,
+                          int* n_issued) {
+  MOE_REQUIRE(layer->host_pinned, "prefetch requested but the layer has no pinned copies");
+  size_t used = 0;
+  for (Slot& sl : group) sl.valid = false;
+  for (int e = 0; e < s.E && used < group.size(); ++e) {
+    if (!bit(mask, e)) continue;
+    const moe_expert_ptrs& src = layer->host_pinned[e];
+    MOE_REQUIRE(src.Wg && src.Wu && src.Wd, "prefetch of expert %d without a pinned copy", e);
+    moe_status st = queue_copy(c, s, group[used], src, layer->layer_id, e, stream);
+    if (st != MOE_OK) return st;
+    ++used;
+  }
+  *n_issued = (int)used;
+  return MOE_OK;
+}
+
 }  // namespace
 
 }  // namespace moe
@@ -256,6 +282,9 @@ extern "C" moe_status moe_create(const moe_shape* max_shape, int32_t n_ondemand_
     MOE_HIP(hipEventCreateWithFlags(&c->ev_counts, hipEventDisableTiming));
     MOE_HIP(hipHostMalloc(reinterpret_cast<void**>(&c->host_counts), MOE_MAX_E * sizeof(int32_t),
                           hipHostMallocDefault));
+    MOE_HIP(hipHostMalloc(reinterpret_cast<void**>(&c->export_host), MOE_MAX_E * sizeof(int32_t),
+                          hipHostMallocDefault));
+    MOE_HIP(hipEventCreateWithFlags(&c->ev_export, hipEventDisableTiming));
     c->ondemand.resize(n_ondemand_slots);
     for (auto& s : c->ondemand) {
       moe_status r = moe::make_slot(s, 3 * c->matrix_bytes);
@@ -296,6 +325,8 @@ extern "C" moe_status moe_destroy(moe_ctx* c) {
   for (auto& e : c->phase_free) (void)hipEventDestroy(e);
   if (c->ev_counts) (void)hipEventDestroy(c->ev_counts);
   if (c->host_counts) (void)hipHostFree(c->host_counts);
+  if (c->export_host) (void)hipHostFree(c->export_host);
+  if (c->ev_export) (void)hipEventDestroy(c->ev_export);
   if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
   delete c;
   return MOE_OK;
@@ -384,6 +415,13 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
   PHASE_MARK(1);
   st = launch_permute(s, topk_idx, count, offset, perm, inv_perm, stream);
   if (st != MOE_OK) return st;
+  if (c->export_counts) {
+    // for a scheduler on the host: the counts travel while the FFN runs, and
+    // nobody waits for them here (moe_layer_counts does)
+    MOE_HIP(hipMemcpyAsync(c->export_host, count, s.E * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+    MOE_HIP(hipEventRecord(c->ev_export, stream));
+    c->export_n = s.E;
+  }
   PHASE_MARK(2);
 
   ExpertTable tab;
@@ -571,23 +609,44 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
 
   // prefetch for the next layer, behind every on-demand copy queued above
   if (next_layer && host_prefetch_next_mask && !nxt.empty()) {
-    MOE_REQUIRE(next_layer->host_pinned, "moe_layer_forward: prefetch requested but next layer has no pinned copies");
-    size_t used = 0;
-    for (Slot& sl : nxt) sl.valid = false;
-    for (int e = 0; e < s.E && used < nxt.size(); ++e) {
-      if (!bit(host_prefetch_next_mask, e)) continue;
-      const moe_expert_ptrs& src = next_layer->host_pinned[e];
-      MOE_REQUIRE(src.Wg && src.Wu && src.Wd, "moe_layer_forward: prefetch of expert %d without a pinned copy", e);
-      st = queue_copy(c, s, nxt[used], src, next_layer->layer_id, e, stream);
-      if (st != MOE_OK) return st;
-      ++used;
-      if (stats) {
-        stats->n_prefetch_issued += 1;
-        stats->bytes_prefetch += (int64_t)(3 * mb);
-      }
+    int issued = 0;
+    st = issue_prefetch(c, s, nxt, next_layer, host_prefetch_next_mask, stream, &issued);
+    if (st != MOE_OK) return st;
+    if (stats) {
+      stats->n_prefetch_issued += issued;
+      stats->bytes_prefetch += (int64_t)issued * (int64_t)(3 * mb);
     }
   }
   c->cur_group ^= 1;
+  return MOE_OK;
+}
+
+extern "C" moe_status moe_prefetch(moe_ctx* c, const moe_shape* shape, const moe_layer_desc* next_layer,
+                                   const uint64_t* host_prefetch_mask, void* stream_,
+                                   int32_t* n_issued) {
+  using namespace moe;
+  moe_status st = check_shape(shape, "moe_prefetch");
+  if (st != MOE_OK) return st;
+  MOE_REQUIRE(c && next_layer && host_prefetch_mask, "moe_prefetch: NULL argument");
+  MOE_REQUIRE((size_t)shape->H * shape->F * elem_size(*shape) <= c->matrix_bytes,
+              "moe_prefetch: expert larger than the context's slots");
+  if (n_issued) *n_issued = 0;
+  // the group the NEXT moe_layer_forward call reads
+  std::vector<Slot>& tgt = c->prefetch[c->cur_group];
+  if (tgt.empty()) return MOE_OK;
+  int issued = 0;
+  st = issue_prefetch(c, *shape, tgt, next_layer, host_prefetch_mask, static_cast<hipStream_t>(stream_),
+                      &issued);
+  if (n_issued) *n_issued = issued;
+  return st;
+}
+
+extern "C" moe_status moe_layer_counts(moe_ctx* c, int32_t* host_count, int32_t E) {
+  MOE_REQUIRE(c && host_count, "moe_layer_counts: NULL argument");
+  MOE_REQUIRE(c->export_n > 0, "moe_layer_counts: no layer has exported its counts (set MOE_OPT_EXPORT_COUNTS first)");
+  MOE_REQUIRE(E == c->export_n, "moe_layer_counts: the last layer had %d experts, not %d", c->export_n, E);
+  MOE_HIP(hipEventSynchronize(c->ev_export));
+  for (int e = 0; e < E; ++e) host_count[e] = c->export_host[e];
   return MOE_OK;
 }
 
@@ -688,6 +747,9 @@ extern "C" moe_status moe_set_option(moe_ctx* c, int32_t option, int64_t value) 
   switch (option) {
     case MOE_OPT_SYNC_COPIES:
       c->sync_copies = value != 0;
+      return MOE_OK;
+    case MOE_OPT_EXPORT_COUNTS:
+      c->export_counts = value != 0;
       return MOE_OK;
     case MOE_OPT_COPY_SPLIT:
       MOE_REQUIRE(value == 1 || value == 3, "moe_set_option: copy split must be 1 or 3");

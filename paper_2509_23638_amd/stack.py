@@ -85,6 +85,8 @@ class StreamedStack:
                 dev=(d["Wg"], d["Wu"], d["Wd"]), pinned=(h["Wg"], h["Wu"], h["Wd"]), layer_id=l))
         self._norm = None
         self._pred = torch.zeros(E, dtype=torch.int32, device="cuda")
+        self._pred_host = None
+        self._pred_event = None
         self._cur = torch.zeros(E, dtype=torch.int32, device="cuda")
         self._in_slot = [set() for _ in range(self.n_layers)]   # experts prefetched for layer l
         self.sched_log = {"n_decisions": 0, "n_prefetch_planned": 0, "f_sum": 0.0}
@@ -145,37 +147,64 @@ class StreamedStack:
         B.moe_predict_counts(self.shape, x_norm, Wr, b, into, self.ws)
         return into.cpu().numpy()
 
+    def _predict_async(self, l_router: int, x_norm: torch.Tensor):
+        """Queue the gate-based prediction and the copy of its E counts to pinned
+        host memory; nobody waits here."""
+        if self._pred_host is None:
+            self._pred_host = torch.empty(self.shape.E, dtype=torch.int32, pin_memory=True)
+            self._pred_event = torch.cuda.Event()
+        Wr, b = self.layers[l_router].keep[0], self.layers[l_router].keep[1]
+        B.moe_predict_counts(self.shape, x_norm, Wr, b, self._pred, self.ws)
+        self._pred_host.copy_(self._pred, non_blocking=True)
+        self._pred_event.record()
+
+    def _predict_wait(self) -> np.ndarray:
+        self._pred_event.synchronize()
+        return self._pred_host.numpy().copy()
+
     def step_online(self, X: torch.Tensor, policy: str, costs: Optional[B.moe_presched_costs] = None,
-                    n_prefetch: int = 2, wrap_prefetch: bool = False):
+                    n_prefetch: int = 2, wrap_prefetch: bool = False, want_stats: bool = True):
         """One pass with the prefetch set decided online, layer by layer:
 
         ``gate_topn``  -- the ``n_prefetch`` non-resident experts of the next
                           layer with the most predicted tokens (gate-based
                           prediction from this layer's input);
         ``presched``   -- the same prediction fed to PreSched together with this
-                          layer's own pending experts; the plan's prefetch list
+                          layer's own pending experts (its actual token counts,
+                          exported by the layer call); the plan's prefetch list
                           (cut to the slots available) is issued;
         ``none``       -- on-demand loads only.
-        Returns (x_final, list of per-layer stats)."""
+
+        Order per layer: the prediction is queued ahead of the layer, the layer
+        is queued, and only then does the host wait for the (long finished)
+        prediction, decide, and queue the prefetch as a call of its own -- so the
+        decision runs in the shadow of the layer's GPU work and the copies start
+        while that layer computes.  Returns (x_final, list of per-layer stats;
+        ``n_prefetch_issued`` / ``bytes_prefetch`` are filled in here)."""
         E = self.shape.E
         if self._norm is None or self._norm.shape != X.shape:
             self._norm = torch.empty_like(X)
             self._bufs = [torch.empty_like(X), torch.empty_like(X)]
+        self.ctx.set_export_counts(policy == "presched")
+        expert_bytes = 3 * self.shape.H * self.shape.F * (2 if self.shape.dtype == B.MOE_BF16 else 4)
         x = X
         stats = []
         for l in range(self.n_layers):
             B.moe_rmsnorm(self.shape, x, self._norm)
             out = self._bufs[l & 1]
             nxt = l + 1 if l + 1 < self.n_layers else (0 if wrap_prefetch else None)
-            pm = None
-            if nxt is not None and policy != "none":
-                pred = self.predicted_counts(nxt, self._norm, self._pred)
-                cand = B.moe_pending_experts(pred, self.resident[nxt])
+            online = nxt is not None and policy != "none"
+            if online:
+                self._predict_async(nxt, self._norm)
+            st = self.layer_forward(l, self._norm, out, residual=x, want_stats=want_stats)
+            in_slot = [e in self._in_slot[l] for e in range(E)]   # prefetched for this layer: not pending
+            self._in_slot[l] = set()
+            if online:
+                cand = B.moe_pending_experts(self._predict_wait(), self.resident[nxt])
                 if policy == "gate_topn":
                     chosen = B.moe_prefetch_hottest(cand, n_prefetch)
                 elif policy == "presched":
-                    mine = self.predicted_counts(l, self._norm, self._cur)
-                    in_slot = [e in self._in_slot[l] for e in range(E)]
+                    mine = self.ctx.layer_counts(E)
                     cur = B.moe_pending_experts(mine, self.resident[l], in_slot)
                     plan = B.moe_presched(costs, cur, cand)
                     chosen = list(plan.prefetch[:min(plan.n_prefetch, n_prefetch)])
@@ -186,11 +215,13 @@ class StreamedStack:
                     raise ValueError(policy)
                 pm = np.zeros(E, dtype=bool)
                 pm[chosen] = True
+                issued = B.moe_prefetch(self.ctx, self.shape, self.layers[nxt], pm)
                 self._in_slot[nxt] = set(chosen)
-            st = self.layer_forward(l, self._norm, out, residual=x, prefetch_next_mask=pm,
-                                    next_l=nxt if pm is not None else None)
-            self._in_slot[l] = set()
-            stats.append(st)
+                if st is not None:
+                    st["n_prefetch_issued"] += issued
+                    st["bytes_prefetch"] += issued * expert_bytes
+            if st is not None:
+                stats.append(st)
             x = out
         return x, stats
 

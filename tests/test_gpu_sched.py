@@ -99,5 +99,13 @@ def test_online_policies_leave_the_output_bitwise_unchanged(B, policy):
         assert 0 < hits <= issued
     if policy == "presched":
         assert stack.sched_log["n_decisions"] == cfg.steps * cfg.layers
+    # and without stats (no host wait where every non-resident expert was prefetched)
+    X = to_dev(make_hidden(cfg, step=0))
+    want, _ = ref_stack.step(X, want_stats=False)
+    want = want.clone()
+    got, stats = stack.step_online(X, policy, costs=costs, n_prefetch=2, wrap_prefetch=True,
+                                   want_stats=False)
+    torch.cuda.synchronize()
+    assert stats == [] and torch.equal(got.view(torch.int16), want.view(torch.int16))
     stack.close()
     ref_stack.close()

@@ -176,3 +176,45 @@ def test_miss_without_ondemand_slots_is_an_error(B, layers):
     assert ei.value.status == -5
     torch.cuda.synchronize()
     stack.close()
+
+
+@pytest.mark.parametrize("layout", ["row_major", "tiled"])
+def test_prefetch_as_a_call_of_its_own_and_exported_counts(B, layers, layout):
+    """moe_prefetch between two layer calls does what the prefetch arguments of
+    the first call do (same hits, same copies, same bits), and with
+    MOE_OPT_EXPORT_COUNTS the host gets every layer's token counts."""
+    from paper_2509_23638_amd.stack import StreamedStack
+    sh = B.make_shape(CFG.T, CFG.H, CFG.E, CFG.k, CFG.F, CFG.S, CFG.dtype, layout)
+    res = [make_residency_mask(CFG, l) for l in range(CFG.layers)]
+    a = StreamedStack(sh, layers, res, 2, 2)      # prefetch through the layer call
+    b = StreamedStack(sh, layers, res, 2, 2)      # prefetch through moe_prefetch
+    with pytest.raises(B.MoEError):
+        b.ctx.layer_counts(CFG.E)                 # nothing exported yet
+    b.ctx.set_export_counts(True)
+    xbytes = 3 * CFG.H * CFG.F * 2
+    for step in range(CFG.steps):
+        X0 = make_hidden(CFG, step=step)
+        trace = _oracle_trace(layers, X0)
+        _, pf = _masks(trace, step, "predicted")
+        for l in range(CFG.layers):
+            inp = to_dev(trace[l]["inp"])
+            out_a, out_b = torch.empty_like(inp), torch.empty_like(inp)
+            nxt = l + 1 if pf[l] is not None else None
+            st_a = a.layer_forward(l, inp, out_a, prefetch_next_mask=pf[l], next_l=nxt)
+            st_b = b.layer_forward(l, inp, out_b)
+            counts = b.ctx.layer_counts(CFG.E)
+            issued = B.moe_prefetch(b.ctx, sh, b.layers[nxt], pf[l]) if nxt is not None else 0
+            torch.cuda.synchronize()
+            assert np.array_equal(counts, np.bincount(trace[l]["topk_idx"].reshape(-1), minlength=CFG.E))
+            assert issued == st_a["n_prefetch_issued"] and st_b["n_prefetch_issued"] == 0
+            for key in ("n_active", "n_resident", "n_hit", "n_miss", "n_wasted", "bytes_on_demand"):
+                assert st_a[key] == st_b[key], (step, l, key)
+            assert torch.equal(out_a.view(torch.int16), out_b.view(torch.int16))
+    ta, tb = a.ctx.stream_totals(), b.ctx.stream_totals()
+    assert ta["n_copies"] == tb["n_copies"] and ta["bytes"] == tb["bytes"] == ta["n_copies"] * xbytes
+    with pytest.raises(B.MoEError):
+        b.ctx.layer_counts(CFG.E + 1)
+    with pytest.raises(B.MoEError):
+        B.moe_prefetch(b.ctx, sh, b.layers[0], [bool(r) for r in res[0]])   # resident experts: no pinned copy
+    a.close()
+    b.close()
