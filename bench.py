@@ -44,7 +44,7 @@ def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=60)
-    ap.add_argument("--warmup", type=int, default=12)
+    ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--tokens", type=int, default=64, help="decode batch (tokens per step)")
     ap.add_argument("--weight-sets", type=int, default=3,
                     help="distinct layers' weights rotated through (cache defeat)")
@@ -573,7 +573,7 @@ def main():
         plan = [("c2_mixtral", t, args.weight_sets) for t in (1, 8, 256)] + \
                [(w, get_config(w).T, 2) for w in ("c3_finegrained", "c4_dsv2lite_prefill", "c6_qwen3_a3b")]
         for w, t, sets in plan:
-            o = run_layer(args, torch, B, w, t, args.other_steps, 5, sets, False)
+            o = run_layer(args, torch, B, w, t, args.other_steps, 30, sets, False)
             others.append({"workload": w, "tokens": t, "ms_per_step": o["ms_per_step"],
                            "ms_per_step_median": o["ms_per_step_median"],
                            "tokens_per_s": o["tokens_per_s"], "active_experts": o["active_experts"],
