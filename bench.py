@@ -419,6 +419,7 @@ def run_layer(args, torch, B, workload, T, steps, warmup, weight_sets, headline)
 
     es = cfg.itemsize
     rows = cfg.rows
+    ys = 2 if B.moe_layer_y_dtype(sh) == torch.bfloat16 else 4   # bytes per element of Y in this block
 
     def gate_up_bytes(na):
         return (na + cfg.S) * 2 * cfg.F * cfg.H * es + T * cfg.H * es + rows * cfg.F * es
@@ -428,7 +429,7 @@ def run_layer(args, torch, B, workload, T, steps, warmup, weight_sets, headline)
                 + 2 * T * cfg.H * es                        # X in, out
                 + cfg.E * cfg.H * es                        # router weights
                 + 2 * rows * cfg.F * es                     # h written, read
-                + 2 * rows * cfg.H * 4)                     # Y written, read (fp32)
+                + 2 * rows * cfg.H * ys)                    # Y written, read
 
     for i in range(warmup):
         B.moe_layer_forward(ctx, sh, layers[i % len(layers)], X, out, ws)

@@ -241,6 +241,12 @@ typedef struct {
  * router's counts before it can queue copies; with every expert resident or
  * prefetched and stats == NULL it never blocks.
  *   out = block output (+ residual if given), [T,H] storage dtype.
+ * Rounding points between the router and `out` (bf16 storage): h is rounded to
+ * bf16 once; the rows of Y stay float32 up to the combine -- except at the
+ * shapes for which moe_layer_y_dtype() answers MOE_BF16 (prefill sizes: about
+ * a hundred rows per expert and more), where each expert's output row is
+ * rounded to bf16 before the weighted sum, as a model that runs its experts as
+ * separate bf16 modules does; the sum itself is float32 and rounded once.
  *   host_resident_mask / host_prefetch_next_mask: HOST words, ceil(E/64) each;
  *     NULL resident mask = all resident; NULL prefetch mask = none.
  *   next_layer may be NULL.  stats may be NULL. */
@@ -376,12 +382,23 @@ moe_status moe_probe_read_nt(const void* src, size_t bytes, void* sink4, void* s
  * over all of them.  Returns a static string, "" for an invalid request. */
 const char* moe_ffn_kernel_name(const moe_shape* shape, int32_t phase, int32_t n_groups);
 
+/* Element type of the rows of Y that moe_layer_forward (and
+ * moe_layer_forward_static) keeps in the workspace between the down projection
+ * and the combine for `shape`: MOE_F32, or MOE_BF16 where the down projection
+ * runs its prefill form (there Y is the largest tensor the block writes and
+ * reads back, and half its bytes are worth more than its last mantissa bits: the
+ * block's output stays within the bf16 tolerance either way).  Depends on the
+ * shape alone.  moe_grouped_ffn and moe_combine always exchange float32 rows.
+ * Returns -1 for an invalid shape. */
+int32_t moe_layer_y_dtype(const moe_shape* shape);
+
 /* Views into a workspace after moe_layer_forward (device pointers into
- * `workspace`; for tests and harnesses).  Any output pointer may be NULL. */
+ * `workspace`; for tests and harnesses).  Any output pointer may be NULL.
+ * *Y points at [T*k + S*T, H] rows of the type moe_layer_y_dtype() names. */
 moe_status moe_workspace_views(const moe_shape* shape, void* workspace,
                                int32_t** topk_idx, float** topk_w,
                                int32_t** count, int32_t** offset,
-                               int32_t** perm, int32_t** inv_perm, float** Y);
+                               int32_t** perm, int32_t** inv_perm, void** Y);
 
 #ifdef __cplusplus
 }

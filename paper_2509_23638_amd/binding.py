@@ -102,6 +102,8 @@ _lib.moe_version.restype = C.c_char_p
 _lib.moe_last_error.restype = C.c_char_p
 _lib.moe_ffn_kernel_name.restype = C.c_char_p
 _lib.moe_ffn_kernel_name.argtypes = [_SH, C.c_int32, C.c_int32]
+_lib.moe_layer_y_dtype.restype = C.c_int32
+_lib.moe_layer_y_dtype.argtypes = [_SH]
 _lib.moe_workspace_bytes.restype = C.c_size_t
 _lib.moe_workspace_bytes.argtypes = [_SH]
 _lib.moe_route.argtypes = [_SH, _P, _P, _P, _P, _P, _P, _P, _P]
@@ -155,12 +157,21 @@ EXPORTS = ["moe_version", "moe_last_error", "moe_workspace_bytes", "moe_route", 
            "moe_rmsnorm", "moe_set_option", "moe_pack_weights",
            "moe_counter_add", "moe_hot_table", "moe_predict_counts", "moe_presched",
            "moe_ffn_kernel_name", "moe_layer_forward_static", "moe_static_workspace_bytes",
-           "moe_pending_experts", "moe_prefetch_hottest", "moe_prefetch", "moe_layer_counts"]
+           "moe_pending_experts", "moe_prefetch_hottest", "moe_prefetch", "moe_layer_counts",
+           "moe_layer_y_dtype"]
 
 
 def _check(st: int):
     if st != 0:
         raise MoEError(st, _lib.moe_last_error().decode())
+
+
+def moe_layer_y_dtype(shape) -> torch.dtype:
+    """Element type of the rows of Y that moe_layer_forward leaves in the workspace."""
+    d = _lib.moe_layer_y_dtype(C.byref(shape))
+    if d < 0:
+        raise MoEError(-1, _lib.moe_last_error().decode())
+    return torch.bfloat16 if d == MOE_BF16 else torch.float32
 
 
 def moe_ffn_kernel_name(shape, phase: int, n_groups: int) -> str:
@@ -469,7 +480,7 @@ def moe_workspace_views(shape, workspace: torch.Tensor) -> dict:
     spec = [("topk_idx", torch.int32, (shape.T, shape.k)), ("topk_w", torch.float32, (shape.T, shape.k)),
             ("count", torch.int32, (shape.E,)), ("offset", torch.int32, (shape.E + 1,)),
             ("perm", torch.int32, (A,)), ("inv_perm", torch.int32, (A,)),
-            ("Y", torch.float32, (rows, shape.H))]
+            ("Y", moe_layer_y_dtype(shape), (rows, shape.H))]
     out = {}
     for p, (name, dt, shp) in zip(ptrs, spec):
         off = p.value - base

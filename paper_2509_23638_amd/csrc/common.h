@@ -84,16 +84,19 @@ moe_status launch_grouped_ffn(const moe_shape& s, const void* X, const int32_t* 
 moe_status launch_ffn_gate_up(const moe_shape& s, const void* X, const int32_t* perm,
                               const int32_t* offset, const ExpertTable& tab,
                               const GroupList& groups, const FfnScratch& scratch, hipStream_t stream);
+// y_bf16: the rows of Y are bf16 instead of float32 (only where layer_y_bf16()
+// says so; the separate entry points always exchange float32 rows).
+bool layer_y_bf16(const moe_shape& s);
 moe_status launch_ffn_down(const moe_shape& s, const FfnScratch& scratch, const int32_t* perm,
                            const int32_t* offset, const ExpertTable& tab, const GroupList& groups,
-                           float* Y, hipStream_t stream);
+                           void* Y, hipStream_t stream, bool y_bf16);
 moe_status launch_ffn_gated(const moe_shape& s, const void* X, const int32_t* perm,
                             const int32_t* offset, const ExpertTable& tab, const GroupList& groups,
-                            float* Y, const FfnScratch& scratch, hipStream_t stream,
-                            hipEvent_t wait_gu, hipEvent_t wait_d, hipEvent_t mid);
-moe_status launch_combine(const moe_shape& s, const float* Y, const float* topk_w,
+                            void* Y, const FfnScratch& scratch, hipStream_t stream,
+                            hipEvent_t wait_gu, hipEvent_t wait_d, hipEvent_t mid, bool y_bf16);
+moe_status launch_combine(const moe_shape& s, const void* Y, const float* topk_w,
                           const int32_t* inv_perm, const void* residual, void* out,
-                          hipStream_t stream);
+                          hipStream_t stream, bool y_bf16);
 
 // ---- device helpers -------------------------------------------------------
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) {

@@ -81,7 +81,7 @@ extern "C" size_t moe_workspace_bytes(const moe_shape* shape) {
 extern "C" moe_status moe_workspace_views(const moe_shape* shape, void* workspace,
                                           int32_t** topk_idx, float** topk_w, int32_t** count,
                                           int32_t** offset, int32_t** perm, int32_t** inv_perm,
-                                          float** Y) {
+                                          void** Y) {
   moe_status st = moe::check_shape(shape, "moe_workspace_views");
   if (st != MOE_OK) return st;
   if (!workspace) return moe::fail(MOE_ERR_WORKSPACE, "moe_workspace_views: NULL workspace");
@@ -93,6 +93,6 @@ extern "C" moe_status moe_workspace_views(const moe_shape* shape, void* workspac
   if (offset) *offset = reinterpret_cast<int32_t*>(w + L.offset);
   if (perm) *perm = reinterpret_cast<int32_t*>(w + L.perm);
   if (inv_perm) *inv_perm = reinterpret_cast<int32_t*>(w + L.inv_perm);
-  if (Y) *Y = reinterpret_cast<float*>(w + L.y);
+  if (Y) *Y = w + L.y;
   return MOE_OK;
 }

@@ -1397,7 +1397,8 @@ using Tag = std::integral_constant<int, V>;
 
 // NT = token tiles multiplied (4, 8, 12 or 16): a compile-time bound.
 // R = (K/64 - 2 - kWideTail) % kWideWeightSets.  ONCE: no other block reads these weight tiles.
-template <int MODE, int NT, int R, bool ONCE>
+// YB (down only): the rows of Y are rounded to bf16 on the way out (half the store bytes).
+template <int MODE, int NT, int R, bool ONCE, bool YB>
 __device__ __forceinline__ void ffn_wide_block(const FfnArgs& a, const ExpertTable& tab,
                                                const TileItem& it, bool has_next,
                                                const TileItem& nxt, ActRsrc rsrc,
@@ -1551,6 +1552,15 @@ __device__ __forceinline__ void ffn_wide_block(const FfnArgs& a, const ExpertTab
         pk.x = pack_bf16x2(hv[0], hv[1]);
         pk.y = pack_bf16x2(hv[2], hv[3]);
         *reinterpret_cast<uint2*>(h + (size_t)p * a.N + nrow[0] + 4 * g) = pk;
+      } else if (YB) {
+        uint16_t* y = static_cast<uint16_t*>(a.out);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          uint2 pk;
+          pk.x = pack_bf16x2(acc[i][j][0], acc[i][j][1]);
+          pk.y = pack_bf16x2(acc[i][j][2], acc[i][j][3]);
+          *reinterpret_cast<uint2*>(y + (size_t)p * a.N + nrow[i] + 4 * g) = pk;
+        }
       } else {
         float* y = static_cast<float*>(a.out);
 #pragma unroll
@@ -1577,7 +1587,7 @@ __device__ __forceinline__ void ffn_wide_block(const FfnArgs& a, const ExpertTab
   }
 }
 
-template <int MODE, int R>
+template <int MODE, int R, bool YB>
 __global__ __launch_bounds__(kWideThreads, 1) void ffn_wide_kernel(FfnArgs a, ExpertTable tab,
                                                                    GroupList groups,
                                                                    long long act_rows) {
@@ -1619,18 +1629,18 @@ __global__ __launch_bounds__(kWideThreads, 1) void ffn_wide_kernel(FfnArgs a, Ex
     bool done = false;
     if constexpr (MODE == kGateUp) {
       if (it.single) {
-        if (tiles <= 4) ffn_wide_block<MODE, 4, R, true>(a, tab, it, has_next, nxt, rsrc, src, ring);
-        else if (tiles <= 8) ffn_wide_block<MODE, 8, R, true>(a, tab, it, has_next, nxt, rsrc, src, ring);
-        else if (tiles <= 12) ffn_wide_block<MODE, 12, R, true>(a, tab, it, has_next, nxt, rsrc, src, ring);
-        else ffn_wide_block<MODE, 16, R, true>(a, tab, it, has_next, nxt, rsrc, src, ring);
+        if (tiles <= 4) ffn_wide_block<MODE, 4, R, true, YB>(a, tab, it, has_next, nxt, rsrc, src, ring);
+        else if (tiles <= 8) ffn_wide_block<MODE, 8, R, true, YB>(a, tab, it, has_next, nxt, rsrc, src, ring);
+        else if (tiles <= 12) ffn_wide_block<MODE, 12, R, true, YB>(a, tab, it, has_next, nxt, rsrc, src, ring);
+        else ffn_wide_block<MODE, 16, R, true, YB>(a, tab, it, has_next, nxt, rsrc, src, ring);
         done = true;
       }
     }
     if (!done) {
-      if (tiles <= 4) ffn_wide_block<MODE, 4, R, false>(a, tab, it, has_next, nxt, rsrc, src, ring);
-      else if (tiles <= 8) ffn_wide_block<MODE, 8, R, false>(a, tab, it, has_next, nxt, rsrc, src, ring);
-      else if (tiles <= 12) ffn_wide_block<MODE, 12, R, false>(a, tab, it, has_next, nxt, rsrc, src, ring);
-      else ffn_wide_block<MODE, 16, R, false>(a, tab, it, has_next, nxt, rsrc, src, ring);
+      if (tiles <= 4) ffn_wide_block<MODE, 4, R, false, YB>(a, tab, it, has_next, nxt, rsrc, src, ring);
+      else if (tiles <= 8) ffn_wide_block<MODE, 8, R, false, YB>(a, tab, it, has_next, nxt, rsrc, src, ring);
+      else if (tiles <= 12) ffn_wide_block<MODE, 12, R, false, YB>(a, tab, it, has_next, nxt, rsrc, src, ring);
+      else ffn_wide_block<MODE, 16, R, false, YB>(a, tab, it, has_next, nxt, rsrc, src, ring);
     }
     if (!has_next) break;
     it = nxt;
@@ -1638,11 +1648,11 @@ __global__ __launch_bounds__(kWideThreads, 1) void ffn_wide_kernel(FfnArgs a, Ex
   }
 }
 
-template <int MODE, int R = 0>
+template <int MODE, bool YB, int R = 0>
 struct WideKernels {
   static const void* get(int r) {
-    if (r == R) return reinterpret_cast<const void*>(&ffn_wide_kernel<MODE, R>);
-    if constexpr (R + 1 < kWideWeightSets) return WideKernels<MODE, R + 1>::get(r);
+    if (r == R) return reinterpret_cast<const void*>(&ffn_wide_kernel<MODE, R, YB>);
+    if constexpr (R + 1 < kWideWeightSets) return WideKernels<MODE, YB, R + 1>::get(r);
     return nullptr;
   }
 };
@@ -1706,7 +1716,11 @@ hipError_t tile_attributes() {
                           hipFuncAttributeMaxDynamicSharedMemorySize, kTileLds);
   if (e != hipSuccess) return e;
   for (int r = 0; r < kWideWeightSets; ++r) {
-    e = hipFuncSetAttribute(WideKernels<MODE>::get(r), hipFuncAttributeMaxDynamicSharedMemorySize,
+    e = hipFuncSetAttribute(WideKernels<MODE, false>::get(r), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            kWideLds);
+    if (e != hipSuccess) return e;
+    if (MODE != kDown) continue;
+    e = hipFuncSetAttribute(WideKernels<kDown, true>::get(r), hipFuncAttributeMaxDynamicSharedMemorySize,
                             kWideLds);
     if (e != hipSuccess) return e;
   }
@@ -1715,7 +1729,9 @@ hipError_t tile_attributes() {
 
 template <int MODE>
 moe_status launch_tile(const moe_shape& s, const FfnArgs& args, const ExpertTable& tab,
-                       const GroupList& groups, hipStream_t stream, bool wide) {
+                       const GroupList& groups, hipStream_t stream, bool wide, bool y_bf16 = false) {
+  if (y_bf16 && !(wide && MODE == kDown))
+    return fail(MOE_ERR_UNSUPPORTED, "bf16 rows of Y exist for the prefill form of the down projection only");
   int dev = 0;
   MOE_HIP(hipGetDevice(&dev));
   if (dev < 0 || dev >= kMaxDevices) return fail(MOE_ERR_UNSUPPORTED, "device index %d out of range", dev);
@@ -1746,8 +1762,8 @@ moe_status launch_tile(const moe_shape& s, const FfnArgs& args, const ExpertTabl
     FfnArgs wargs = args;
     void* params[] = {&wargs, const_cast<ExpertTable*>(&tab), const_cast<GroupList*>(&groups), &act_rows};
     const int r = (args.K / kTileK - 2 - kWideTail) % kWideWeightSets;
-    MOE_HIP(hipLaunchKernel(WideKernels<MODE>::get(r), dim3(grid), dim3(kWideThreads), params,
-                            kWideLds, stream));
+    const void* kernel = y_bf16 ? WideKernels<kDown, true>::get(r) : WideKernels<MODE, false>::get(r);
+    MOE_HIP(hipLaunchKernel(kernel, dim3(grid), dim3(kWideThreads), params, kWideLds, stream));
   } else {
     if (small)   // every bucket, a shared expert's too, has at most T rows
       hipLaunchKernelGGL((ffn_tile_small_kernel<MODE>), dim3(grid), dim3(kThreads), kTileLds, stream,
@@ -2051,6 +2067,17 @@ Variant down_variant(const moe_shape& s) {
   return kStream64;
 }
 
+// Whether moe_layer_forward keeps the rows of Y in bf16 between the down
+// projection and the combine: at the shapes whose down projection runs the
+// prefill form.  There Y is the largest tensor the block writes and reads back
+// (rows x H x 4 bytes: more than the activations and h together), an expert's
+// output rounded to the storage dtype is what a module-by-module bf16 model
+// produces anyway, and the stores are what the down kernel's items wait for.
+// Decided by the shape alone, like the kernel choice.
+bool layer_y_bf16(const moe_shape& s) {
+  return s.dtype == MOE_BF16 && tile_kernel_fits(s) && down_variant(s) == kTile && wide_form(s, 1);
+}
+
 // Phase 1 (gate and up projections, SiLU gate) for the experts in `groups`.
 moe_status launch_ffn_gate_up(const moe_shape& s, const void* X, const int32_t* perm,
                               const int32_t* offset, const ExpertTable& tab,
@@ -2088,8 +2115,10 @@ moe_status launch_ffn_gate_up(const moe_shape& s, const void* X, const int32_t* 
 // Phase 2 (down projection) for the experts in `groups`.
 moe_status launch_ffn_down(const moe_shape& s, const FfnScratch& scratch, const int32_t* perm,
                            const int32_t* offset, const ExpertTable& tab, const GroupList& groups,
-                           float* Y, hipStream_t stream) {
+                           void* Y, hipStream_t stream, bool y_bf16) {
   if (groups.n == 0 || s.T == 0) return MOE_OK;
+  if (y_bf16 && !layer_y_bf16(s))
+    return fail(MOE_ERR_UNSUPPORTED, "bf16 rows of Y are not available for this shape");
   const int A = s.T * s.k;
   const void* h = scratch.h;
   if (s.dtype == MOE_BF16) {
@@ -2098,7 +2127,7 @@ moe_status launch_ffn_down(const moe_shape& s, const FfnScratch& scratch, const 
                s.S > 0 || s.T > 64, split_allowed()};
     const Variant v = down_variant(s);
     if (v == kTile && tile_kernel_fits(s)) {
-      return launch_tile<kDown>(s, dn, tab, groups, stream, wide_form(s, 1));
+      return launch_tile<kDown>(s, dn, tab, groups, stream, wide_form(s, 1), y_bf16);
     } else if (v == kHalves) {
       hipLaunchKernelGGL((ffn_stream_kernel<kDownHalves, 4, 1>), dim3(s.H / (kWaves * 16), groups.n, (s.T + 63) / 64),
                          dim3(kThreads), 0, stream, dn, tab, groups);
@@ -2121,7 +2150,7 @@ moe_status launch_ffn_down(const moe_shape& s, const FfnScratch& scratch, const 
     }
   } else {
     const int zb = s.T < 64 ? s.T : 64;
-    F32Args dn{static_cast<const float*>(h), perm, offset, Y, s.T, s.k, s.E, A, s.F, s.H};
+    F32Args dn{static_cast<const float*>(h), perm, offset, static_cast<float*>(Y), s.T, s.k, s.E, A, s.F, s.H};
     hipLaunchKernelGGL((ffn_f32_kernel<kDown>), dim3((s.H + kWaves - 1) / kWaves, groups.n, zb),
                        dim3(kThreads), 0, stream, dn, tab, groups);
   }
@@ -2135,14 +2164,14 @@ moe_status launch_ffn_down(const moe_shape& s, const FfnScratch& scratch, const 
 // (may be NULL) is recorded between the phases.
 moe_status launch_ffn_gated(const moe_shape& s, const void* X, const int32_t* perm,
                             const int32_t* offset, const ExpertTable& tab, const GroupList& groups,
-                            float* Y, const FfnScratch& scratch, hipStream_t stream,
-                            hipEvent_t wait_gu, hipEvent_t wait_d, hipEvent_t mid) {
+                            void* Y, const FfnScratch& scratch, hipStream_t stream,
+                            hipEvent_t wait_gu, hipEvent_t wait_d, hipEvent_t mid, bool y_bf16) {
   if (wait_gu) MOE_HIP(hipStreamWaitEvent(stream, wait_gu, 0));
   moe_status st = launch_ffn_gate_up(s, X, perm, offset, tab, groups, scratch, stream);
   if (st != MOE_OK) return st;
   if (mid) MOE_HIP(hipEventRecord(mid, stream));
   if (wait_d) MOE_HIP(hipStreamWaitEvent(stream, wait_d, 0));
-  return launch_ffn_down(s, scratch, perm, offset, tab, groups, Y, stream);
+  return launch_ffn_down(s, scratch, perm, offset, tab, groups, Y, stream, y_bf16);
 }
 
 moe_status launch_grouped_ffn(const moe_shape& s, const void* X, const int32_t* perm,
@@ -2150,7 +2179,7 @@ moe_status launch_grouped_ffn(const moe_shape& s, const void* X, const int32_t* 
                               const GroupList& groups, float* Y, const FfnScratch& scratch,
                               hipStream_t stream) {
   return launch_ffn_gated(s, X, perm, offset, tab, groups, Y, scratch, stream, nullptr, nullptr,
-                          nullptr);
+                          nullptr, false);
 }
 
 const char* ffn_kernel_name(const moe_shape& s, int phase, int n_groups) {
@@ -2198,6 +2227,11 @@ extern "C" moe_status moe_grouped_ffn(const moe_shape* shape, const void* X, con
   const moe::FfnScratch scratch{static_cast<char*>(workspace) + L.h};
   return moe::launch_grouped_ffn(*shape, X, perm, offset, tab, groups, Y, scratch,
                                  static_cast<hipStream_t>(stream));
+}
+
+extern "C" int32_t moe_layer_y_dtype(const moe_shape* shape) {
+  if (moe::check_shape(shape, "moe_layer_y_dtype") != MOE_OK) return -1;
+  return moe::layer_y_bf16(*shape) ? MOE_BF16 : MOE_F32;
 }
 
 extern "C" const char* moe_ffn_kernel_name(const moe_shape* shape, int32_t phase, int32_t n_groups) {

@@ -380,7 +380,8 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
   int32_t* perm = reinterpret_cast<int32_t*>(w + L.perm);
   int32_t* inv_perm = reinterpret_cast<int32_t*>(w + L.inv_perm);
   const FfnScratch h{w + L.h};
-  float* Y = reinterpret_cast<float*>(w + L.y);
+  void* Y = w + L.y;
+  const bool y_bf16 = layer_y_bf16(s);   // rows of Y in bf16 at prefill sizes (see launch_ffn_down)
   const size_t mb = (size_t)s.H * s.F * elem_size(s);
 
   bool all_resident = true;
@@ -441,7 +442,7 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
     st = launch_ffn_gate_up(s, X, perm, offset, tab, res_groups, h, stream);
     if (st != MOE_OK) return st;
     PHASE_MARK(3);
-    st = launch_ffn_down(s, h, perm, offset, tab, res_groups, Y, stream);
+    st = launch_ffn_down(s, h, perm, offset, tab, res_groups, Y, stream, y_bf16);
     if (st != MOE_OK) return st;
     PHASE_MARK(4);
   } else {
@@ -540,7 +541,7 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
     }
 
     // resident experts first: they need nothing from the link
-    st = launch_ffn_gated(s, X, perm, offset, tab, res_groups, Y, h, stream, join_gu, join_d, nullptr);
+    st = launch_ffn_gated(s, X, perm, offset, tab, res_groups, Y, h, stream, join_gu, join_d, nullptr, y_bf16);
     if (st != MOE_OK) return st;
     // hits still in flight: ONE grouped launch behind the newest of their copies
     // (sub-tensor mode: its gate and up projections landing gates the first
@@ -549,7 +550,7 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
     if (newest && !hits_joined) {
       st = launch_ffn_gated(s, X, perm, offset, tab, hit_groups, Y, h, stream,
                             newest->gu_pending ? newest->copied_gu : newest->copied,
-                            newest->copied, nullptr);
+                            newest->copied, nullptr, y_bf16);
       if (st != MOE_OK) return st;
     }
     for (int e : hits) {
@@ -582,7 +583,8 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
         if (stats) stats->bytes_on_demand += (int64_t)(3 * mb);
       }
       st = launch_ffn_gated(s, X, perm, offset, tab, batch, Y, h, stream,
-                            last->gu_pending ? last->copied_gu : last->copied, last->copied, nullptr);
+                            last->gu_pending ? last->copied_gu : last->copied, last->copied, nullptr,
+                            y_bf16);
       if (st != MOE_OK) return st;
       for (Slot* sl : used) {
         MOE_HIP(hipEventRecord(sl->released, stream));
@@ -602,7 +604,7 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
   // recorded `released`); it becomes the target of the layer after next
   for (Slot& sl : cur) sl.valid = false;
 
-  st = launch_combine(s, Y, topk_w, inv_perm, residual, out, stream);
+  st = launch_combine(s, Y, topk_w, inv_perm, residual, out, stream, y_bf16);
   if (st != MOE_OK) return st;
   PHASE_MARK(5);
 #undef PHASE_MARK
@@ -727,7 +729,8 @@ extern "C" moe_status moe_layer_forward_static(const moe_shape* shape, const moe
   int32_t* perm = reinterpret_cast<int32_t*>(w + L.perm);
   int32_t* inv_perm = reinterpret_cast<int32_t*>(w + L.inv_perm);
   const FfnScratch h{w + L.h};
-  float* Y = reinterpret_cast<float*>(w + L.y);
+  void* Y = w + L.y;
+  const bool y_bf16 = layer_y_bf16(s);   // as in moe_layer_forward: the two must agree bit for bit
   // nothing in the workspace has to start at zero: every kernel below writes
   // what the next one reads (the previous call's contents are simply overwritten)
   st = launch_route(s, X, layer->Wr, layer->bias, topk_idx, topk_w,
@@ -737,9 +740,9 @@ extern "C" moe_status moe_layer_forward_static(const moe_shape* shape, const moe
   if (st != MOE_OK) return st;
   st = launch_ffn_gate_up(s, X, perm, offset, tab, groups, h, stream);
   if (st != MOE_OK) return st;
-  st = launch_ffn_down(s, h, perm, offset, tab, groups, Y, stream);
+  st = launch_ffn_down(s, h, perm, offset, tab, groups, Y, stream, y_bf16);
   if (st != MOE_OK) return st;
-  return launch_combine(s, Y, topk_w, inv_perm, residual, out, stream);
+  return launch_combine(s, Y, topk_w, inv_perm, residual, out, stream, y_bf16);
 }
 
 extern "C" moe_status moe_set_option(moe_ctx* c, int32_t option, int64_t value) {

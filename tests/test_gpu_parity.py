@@ -318,7 +318,7 @@ def _layer_gpu(B, cfg, L, ctx=None, layout="row_major", dev_weights=None, want_r
     res = {"out": O.widen(to_host_bits(out)), "topk_idx": v["topk_idx"].cpu().numpy(),
            "topk_w": v["topk_w"].cpu().numpy(), "count": v["count"].cpu().numpy()}
     if want_rows:
-        res.update(Y=v["Y"].cpu().numpy(), offset=v["offset"].cpu().numpy(),
+        res.update(Y=v["Y"].float().cpu().numpy(), offset=v["offset"].cpu().numpy(),
                    perm=v["perm"].cpu().numpy())
     if own:
         ctx.close()
@@ -561,6 +561,49 @@ def test_layer_forward_c4_prefill_stratified(B, layout, c4_case):
     _check_ffn_rows(cfg, L, L["X"], got, rows)
     assert len(tokens) >= 128
     assert row_rel_err(got["out"][tokens], ref["out"][tokens]) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("name", ["s_bf16_filled_blocks", "s_bf16_filled_blocks_12"])
+def test_prefill_layer_keeps_rows_of_y_in_bf16(B, name, layout):
+    """Where the down projection runs its prefill form the block keeps Y in bf16:
+    those rows must be exactly the float32 rows of moe_grouped_ffn rounded to
+    nearest even (same kernel arithmetic, one more rounding), and the block's
+    output must be the float32 weighted sum of the ROUNDED rows."""
+    cfg = next(c for c in SMALL if c.name == name)
+    L = make_layer(cfg)
+    sh = _shape(B, cfg, layout=layout)
+    assert B.moe_layer_y_dtype(sh) == torch.bfloat16
+    assert B.moe_ffn_kernel_name(sh, 1, cfg.E + cfg.S) == "ffn_wide_kernel<down>"
+    dev_w = _experts_dev(B, L, layout)
+    ctx = B.Context(sh)
+    layer = B.make_layer_desc(sh, to_dev(L["Wr"]), to_dev(L["b"]), dev=dev_w)
+    X = to_dev(L["X"])
+    out = torch.empty_like(X)
+    ws = B.alloc_workspace(sh)
+    B.moe_layer_forward(ctx, sh, layer, X, out, ws)
+    torch.cuda.synchronize()
+    v = B.moe_workspace_views(sh, ws)
+    assert v["Y"].dtype == torch.bfloat16
+    rows = cfg.T * cfg.k + cfg.S * cfg.T
+    Y32 = torch.full((rows, cfg.H), float("nan"), dtype=torch.float32, device="cuda")
+    ws2 = B.alloc_workspace(sh)
+    tab = B.expert_table(sh, *dev_w)
+    B.moe_grouped_ffn(sh, X, v["perm"], v["offset"], tab, None, Y32, ws2)
+    torch.cuda.synchronize()
+    assert torch.isfinite(Y32).all()
+    assert torch.equal(v["Y"].view(torch.int16), Y32.to(torch.bfloat16).view(torch.int16))
+    # the weighted sum of the rounded rows, in float64 (the kernel sums in float32 and rounds once)
+    Yr = v["Y"].double().cpu().numpy()
+    w = v["topk_w"].double().cpu().numpy()
+    inv = v["inv_perm"].cpu().numpy().reshape(cfg.T, cfg.k)
+    A = cfg.T * cfg.k
+    want = (w[:, :, None] * Yr[inv]).sum(axis=1)
+    for s_ in range(cfg.S):
+        want += Yr[A + s_ * cfg.T:A + (s_ + 1) * cfg.T]
+    got = O.widen(to_host_bits(out))
+    assert row_rel_err(got, want) <= 2.0 ** -8       # one bf16 rounding of the sum
+    ctx.close()
 
 
 def test_small_configs_reach_every_ffn_kernel(B):

@@ -69,6 +69,19 @@ def test_the_small_tiled_kernel_is_chosen_by_the_token_count_alone(B):
         assert want in B.moe_ffn_kernel_name(sh, 0, cfg.E)
 
 
+def test_rows_of_y_are_bf16_exactly_where_the_down_projection_runs_its_prefill_form(B):
+    """The block keeps Y in bf16 only at prefill sizes; the decision is the shape's."""
+    import torch
+    for name, T in (("c4_dsv2lite_prefill", None), ("c2_mixtral", 512), ("c2_mixtral", 64), ("c2_mixtral", 256),
+                    ("c3_finegrained", None), ("c5_stack", None), ("c6_qwen3_a3b", None), ("c1_tiny", None)):
+        cfg = get_config(name)
+        sh = B.make_shape(T or cfg.T, cfg.H, cfg.E, cfg.k, cfg.F, cfg.S, cfg.dtype,
+                          "tiled" if cfg.dtype == "bf16" else "row_major")
+        wide = B.moe_ffn_kernel_name(sh, 1, cfg.E + cfg.S) == "ffn_wide_kernel<down>"
+        assert (B.moe_layer_y_dtype(sh) == torch.bfloat16) == wide, name
+    assert B.moe_layer_y_dtype(B.make_shape(2048, 2048, 64, 6, 1408, 2, "bf16", "tiled")) == torch.bfloat16
+
+
 def test_product_build_has_no_tuning_overrides(B):
     """MOE_TUNE_* environment overrides exist only in measurement builds."""
     assert "tuning" not in B.moe_version()
