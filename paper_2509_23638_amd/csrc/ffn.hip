@@ -1259,10 +1259,20 @@ __global__ __launch_bounds__(kThreads, 1) void ffn_tile_small_kernel(FfnArgs a, 
   tile_plan_build<kSmallRows>(plan, a, groups);
   const int slabs = a.N / (MODE == kGateUp ? 64 : 128);
   const int total = plan.first[groups.n] * slabs;
-  const int xcd = blockIdx.x & 7, stride = gridDim.x >> 3;   // grid is a multiple of 8
+  const int xcd = blockIdx.x & 7;   // grid is a multiple of 8
+  int stride = gridDim.x >> 3;
   int local = blockIdx.x >> 3;
   const TileOrder order = tile_order(total, xcd, a.interleave && (plan.sizes & (plan.sizes - 1)) != 0);
-  if (local >= order.count) return;
+  // The walk takes ceil(count / stride) rounds whatever the stride; with the
+  // fewest workgroups that still finish in that many rounds every workgroup
+  // gets the same number of items (one token, two active experts: 56 items per
+  // XCD over 28 workgroups, two each, instead of 24 with two and 8 with one),
+  // and none of them shares the memory system with workgroups that leave early.
+  if (a.split_tail && order.count > 0) {
+    const int rounds = (order.count + stride - 1) / stride;
+    stride = (order.count + rounds - 1) / rounds;
+  }
+  if (local >= min(stride, order.count)) return;
   const int lane = threadIdx.x & (MOE_WAVE - 1), wave = threadIdx.x / MOE_WAVE;
   const int w_adv = a.tiled ? 1024 : kTileK;
 
@@ -1848,7 +1858,7 @@ constexpr int kSplitRows = 32;   // weight rows per workgroup (16 in the one-til
 constexpr int kSplitTok = 32;    // bucket rows per pass (NT <= 2)
 constexpr int kSplitOneTileIds = 16;  // up to this many (token, slot) pairs: the one-tile form
 
-template <int NT, bool ONCE, int NW>
+template <int NT, bool ONCE, int NW, int NWV>
 __device__ __forceinline__ void down_splitk_block(const FfnArgs& a, const uint16_t* Wd, int n0,
                                                   int r0, int row_end, float* red) {
   const int lane = threadIdx.x & (MOE_WAVE - 1), wave = threadIdx.x / MOE_WAVE;
@@ -1863,7 +1873,7 @@ __device__ __forceinline__ void down_splitk_block(const FfnArgs& a, const uint16
     st.b[t] = a.act + (size_t)p * a.K + g * 8;
   }
   const int nchunks = a.K / kChunk;
-  const int per = (nchunks + kWaves - 1) / kWaves;
+  const int per = (nchunks + NWV - 1) / NWV;
   st.run(min(wave * per, nchunks), min((wave + 1) * per, nchunks));
 
   // partial sums -> LDS [wave][t][tile][lane] (float4), then a fixed-order sum
@@ -1874,12 +1884,12 @@ __device__ __forceinline__ void down_splitk_block(const FfnArgs& a, const uint16
   }
   __syncthreads();
   float* y = static_cast<float*>(a.out);
-  for (int q = wave; q < NT * 2; q += kWaves) {  // q = t * 2 + tile
+  for (int q = wave; q < NT * 2; q += NWV) {  // q = t * 2 + tile
     const int t = q >> 1, tile = q & 1;
     if (tile >= NW) continue;
     f32x4 sum = reinterpret_cast<const f32x4*>(red)[((0 * NT + t) * 2 + tile) * MOE_WAVE + lane];
 #pragma unroll
-    for (int w = 1; w < kWaves; ++w) {
+    for (int w = 1; w < NWV; ++w) {
       const f32x4 v = reinterpret_cast<const f32x4*>(red)[((w * NT + t) * 2 + tile) * MOE_WAVE + lane];
       sum[0] += v[0]; sum[1] += v[1]; sum[2] += v[2]; sum[3] += v[3];
     }
@@ -1894,10 +1904,20 @@ __device__ __forceinline__ void down_splitk_block(const FfnArgs& a, const uint16
 // very smallest batches, where at most a handful of experts is active and twice
 // the workgroups put twice the loads in flight.  A row's sum is the same four
 // quarter sums in the same order either way.
-template <int NW>
-__global__ __launch_bounds__(kThreads) void ffn_down_splitk_kernel(FfnArgs a, ExpertTable tab,
-                                                                   GroupList groups) {
-  __shared__ __attribute__((aligned(16))) float red[kWaves * 2 * 2 * MOE_WAVE * 4];  // 16 KiB
+// NWV = wavefronts per workgroup = parts of the contraction (4; with NW = 1 also
+// 8 or 16).  What this kernel needs is loads in flight, and a launch has at most
+// (active experts) x H / 16 workgroups: with one token two experts are active,
+// 512 workgroups of four waves are eight waves per compute unit, each with two
+// 4 KiB chunks of weights on the way, well short of what the memory system
+// takes.  So the fewer (token, slot) pairs a launch has, the more parts the
+// contraction is cut into (the launcher decides from T x k alone); the partial
+// sums still meet in LDS in wave order.
+template <int NW, int NWV>
+__global__ __launch_bounds__(NWV * MOE_WAVE) void ffn_down_splitk_kernel(FfnArgs a, ExpertTable tab,
+                                                                         GroupList groups) {
+  static_assert(NWV == kWaves || NW == 1, "more than four parts only in the one-tile form");
+  constexpr int kMaxNT = NWV == kWaves ? 2 : 1;   // pairs <= 4 with more parts: one token tile
+  __shared__ __attribute__((aligned(16))) float red[NWV * kMaxNT * 2 * MOE_WAVE * 4];
   const int e = groups.id[blockIdx.y];
   int row_begin, row_end;
   if (e < a.E) {
@@ -1912,12 +1932,12 @@ __global__ __launch_bounds__(kThreads) void ffn_down_splitk_kernel(FfnArgs a, Ex
   const uint16_t* Wd = static_cast<const uint16_t*>(tab.Wd[e]);
   const int n0 = blockIdx.x * (16 * NW);
   const bool once = blockIdx.z == 0 && row_end - r0 <= kSplitTok;   // the bucket's only pass
-  if (row_end - r0 <= 16) {
-    if (once) down_splitk_block<1, true, NW>(a, Wd, n0, r0, row_end, red);
-    else down_splitk_block<1, false, NW>(a, Wd, n0, r0, row_end, red);
+  if (kMaxNT == 1 || row_end - r0 <= 16) {
+    if (once) down_splitk_block<1, true, NW, NWV>(a, Wd, n0, r0, row_end, red);
+    else down_splitk_block<1, false, NW, NWV>(a, Wd, n0, r0, row_end, red);
   } else {
-    if (once) down_splitk_block<2, true, NW>(a, Wd, n0, r0, row_end, red);
-    else down_splitk_block<2, false, NW>(a, Wd, n0, r0, row_end, red);
+    if (once) down_splitk_block<kMaxNT, true, NW, NWV>(a, Wd, n0, r0, row_end, red);
+    else down_splitk_block<kMaxNT, false, NW, NWV>(a, Wd, n0, r0, row_end, red);
   }
 }
 
@@ -2134,12 +2154,24 @@ moe_status launch_ffn_down(const moe_shape& s, const FfnScratch& scratch, const 
     } else if (v == kSplitK) {
       const int tok_blocks = (s.T + kSplitTok - 1) / kSplitTok;
       static const char* nw_env = tune_env("MOE_TUNE_SPLITNW");
-      const bool one_tile = nw_env ? nw_env[0] == '1' : (long)s.T * s.k <= kSplitOneTileIds;
-      if (one_tile)
-        hipLaunchKernelGGL(ffn_down_splitk_kernel<1>, dim3(s.H / 16, groups.n, tok_blocks),
+      const long pairs = (long)s.T * s.k;
+      const bool one_tile = nw_env ? nw_env[0] == '1' : pairs <= kSplitOneTileIds;
+      // parts of the contraction (see the kernel): 16 up to two pairs, 8 up to four, else 4.
+      // (Shared experts have T rows each, so they count as well.)
+      static const char* wv_env = tune_env("MOE_TUNE_SPLITWAVES");
+      int parts = (pairs <= 2 && s.T <= 2) ? 16 : (pairs <= 4 && s.T <= 4) ? 8 : 4;
+      if (wv_env) parts = atoi(wv_env);
+      if (one_tile && parts == 16 && pairs <= 16 && s.T <= 16)
+        hipLaunchKernelGGL((ffn_down_splitk_kernel<1, 16>), dim3(s.H / 16, groups.n, tok_blocks),
+                           dim3(16 * MOE_WAVE), 0, stream, dn, tab, groups);
+      else if (one_tile && parts == 8 && pairs <= 16 && s.T <= 16)
+        hipLaunchKernelGGL((ffn_down_splitk_kernel<1, 8>), dim3(s.H / 16, groups.n, tok_blocks),
+                           dim3(8 * MOE_WAVE), 0, stream, dn, tab, groups);
+      else if (one_tile)
+        hipLaunchKernelGGL((ffn_down_splitk_kernel<1, kWaves>), dim3(s.H / 16, groups.n, tok_blocks),
                            dim3(kThreads), 0, stream, dn, tab, groups);
       else
-        hipLaunchKernelGGL(ffn_down_splitk_kernel<2>, dim3(s.H / kSplitRows, groups.n, tok_blocks),
+        hipLaunchKernelGGL((ffn_down_splitk_kernel<2, kWaves>), dim3(s.H / kSplitRows, groups.n, tok_blocks),
                            dim3(kThreads), 0, stream, dn, tab, groups);
     } else if (v != kStream64) {
       hipLaunchKernelGGL((ffn_stream_kernel<kDown, 8, 1>), dim3(s.H / (kWaves * 32), groups.n, (s.T + 127) / 128),
