@@ -113,7 +113,8 @@ struct Streamer {
   int lane, wave;
   int wstep;              // elements from one k-step of a weight tile to the next
   size_t act_off[NT];     // element offset of this lane's activation row per tile
-  static constexpr int NS = (RT == 1 && !kHalves) ? 3 : 2;   // weight chunks held: c .. c+NS-1
+  // weight chunks held: c .. c+NS-1 (the one-tile form has the registers for one more in flight)
+  static constexpr int NS = MODE == kDownNarrow ? 4 : (RT == 1 && !kHalves) ? 3 : 2;
   bf16x8 wreg[NS][kStepsPerChunk][NA];
   uint4 xreg[NS][NH * NT];   // activation fetches in flight, by chunk modulo NS
   f32x4 acc[NA][NT];
@@ -210,11 +211,22 @@ struct Streamer {
     load_act<0>(0);
     load_weights<0>(0);
     if (nchunks > 1) load_act<1>(1);
-    if (NS == 3 && nchunks > 1) load_weights<1>(1);
+    if (NS >= 3 && nchunks > 1) load_weights<1>(1);
+    if (NS >= 4 && nchunks > 2) load_weights<2 % NS>(2);
     store_act<0>(0);
     __syncthreads();
     int c = 0;
-    if (NS == 3) {
+    if (NS == 4) {
+      for (; c + 3 < nchunks; c += 4) {
+        step<0>(c, nchunks);
+        step<1>(c + 1, nchunks);
+        step<2 % NS>(c + 2, nchunks);
+        step<3 % NS>(c + 3, nchunks);
+      }
+      if (c < nchunks) step<0>(c, nchunks);
+      if (c + 1 < nchunks) step<1>(c + 1, nchunks);
+      if (c + 2 < nchunks) step<2 % NS>(c + 2, nchunks);
+    } else if (NS == 3) {
       for (; c + 2 < nchunks; c += 3) {
         step<0>(c, nchunks);
         step<1>(c + 1, nchunks);
