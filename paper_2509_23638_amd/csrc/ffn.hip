@@ -1492,9 +1492,8 @@ __device__ __forceinline__ void ffn_wide_block(const FfnArgs& a, const ExpertTab
   auto stage = [&](int st, auto set_tag, auto remaining_tag, auto rows_tag) {
     constexpr int SET = decltype(set_tag)::value;
     constexpr int D = decltype(remaining_tag)::value;
-    // token blocks this item multiplies: their fetches dealt over the eight waves
-    // (a wave's q-th fetch belongs to token block 4 q + wave / 2)
-    constexpr int NTOK = (NT + 3) / 4;
+    // token blocks this item multiplies: 2 NT fetches of the 32, NT / 4 per wave
+    constexpr int NTOK = NT / 4;
     constexpr bool IW = wide_issue_w(D) > 0, IT = wide_issue_t(D, NTOK) > 0;
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(wide_wait(D, NTOK)) : "memory");
     if (decltype(rows_tag)::value && has_next) {
@@ -1649,30 +1648,22 @@ __global__ __launch_bounds__(kWideThreads, 1) void ffn_wide_kernel(FfnArgs a, Ex
     const int tiles = (min(it.row_end - it.r0, kWideRows) + 15) / 16;
     // gate/up weights of an expert with a single block: non-temporal.  (For the
     // down projection the hint measured slower in this kernel.)
-    // NT = token tiles multiplied: multiples of four, and 13 and 14 between 12 and
-    // 16 (buckets of a prefill layer scatter around their mean, here 192 rows: half
-    // of them need one or two tiles more than twelve, and the full sixteen would
-    // spend a fifth of those blocks' matrix instructions on padding)
-#define WIDE_BLOCK(NT_, ONCE_) ffn_wide_block<MODE, NT_, R, ONCE_, YB>(a, tab, it, has_next, nxt, rsrc, src, ring)
-#define WIDE_BY_TILES(ONCE_)                 \
-  do {                                       \
-    if (tiles <= 4) WIDE_BLOCK(4, ONCE_);    \
-    else if (tiles <= 8) WIDE_BLOCK(8, ONCE_);   \
-    else if (tiles <= 12) WIDE_BLOCK(12, ONCE_); \
-    else if (tiles == 13) WIDE_BLOCK(13, ONCE_); \
-    else if (tiles == 14) WIDE_BLOCK(14, ONCE_); \
-    else WIDE_BLOCK(16, ONCE_);              \
-  } while (0)
     bool done = false;
     if constexpr (MODE == kGateUp) {
       if (it.single) {
-        WIDE_BY_TILES(true);
+        if (tiles <= 4) ffn_wide_block<MODE, 4, R, true, YB>(a, tab, it, has_next, nxt, rsrc, src, ring);
+        else if (tiles <= 8) ffn_wide_block<MODE, 8, R, true, YB>(a, tab, it, has_next, nxt, rsrc, src, ring);
+        else if (tiles <= 12) ffn_wide_block<MODE, 12, R, true, YB>(a, tab, it, has_next, nxt, rsrc, src, ring);
+        else ffn_wide_block<MODE, 16, R, true, YB>(a, tab, it, has_next, nxt, rsrc, src, ring);
         done = true;
       }
     }
-    if (!done) WIDE_BY_TILES(false);
-#undef WIDE_BY_TILES
-#undef WIDE_BLOCK
+    if (!done) {
+      if (tiles <= 4) ffn_wide_block<MODE, 4, R, false, YB>(a, tab, it, has_next, nxt, rsrc, src, ring);
+      else if (tiles <= 8) ffn_wide_block<MODE, 8, R, false, YB>(a, tab, it, has_next, nxt, rsrc, src, ring);
+      else if (tiles <= 12) ffn_wide_block<MODE, 12, R, false, YB>(a, tab, it, has_next, nxt, rsrc, src, ring);
+      else ffn_wide_block<MODE, 16, R, false, YB>(a, tab, it, has_next, nxt, rsrc, src, ring);
+    }
     if (!has_next) break;
     it = nxt;
     local += stride;
