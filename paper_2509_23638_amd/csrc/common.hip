@@ -65,9 +65,9 @@ WorkspaceLayout workspace_layout(const moe_shape& s) {
 
 extern "C" const char* moe_version(void) {
 #ifdef MOE_TUNING
-  return "moe_hotpath 0.2 (gfx950, tuning build: MOE_TUNE_* overrides compiled in)";
+  return "moe_hotpath 0.3 (gfx950, tuning build: MOE_TUNE_* overrides compiled in)";
 #else
-  return "moe_hotpath 0.2 (gfx950)";
+  return "moe_hotpath 0.3 (gfx950)";
 #endif
 }
 
