@@ -46,6 +46,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--tokens", type=int, default=64, help="decode batch (tokens per step)")
+    ap.add_argument("--tokens-all", action="store_true",
+                    help="apply --tokens to every single-layer workload, not only to c2_mixtral")
     ap.add_argument("--weight-sets", type=int, default=3,
                     help="distinct layers' weights rotated through (cache defeat)")
     ap.add_argument("--workload", default="c2_mixtral",
@@ -542,7 +544,7 @@ def main():
 
     if args.workload == "c5_stack":
         return run_c5(args, torch, B)
-    T = args.tokens if args.workload == "c2_mixtral" else get_config(args.workload).T
+    T = args.tokens if (args.workload == "c2_mixtral" or args.tokens_all) else get_config(args.workload).T
     r = run_layer(args, torch, B, args.workload, T, args.steps, args.warmup, args.weight_sets, True)
     cfg = r["_cfg"]
     res = {

@@ -46,9 +46,10 @@ constexpr int kKStep = 32;          // contraction depth of one MFMA
 constexpr int kStepsPerChunk = 4;   // k-steps staged per LDS buffer
 constexpr int kChunk = kKStep * kStepsPerChunk;  // 128
 constexpr int kFragBytes = MOE_WAVE * 16;        // one B fragment in LDS
-// TB = 16-row activation tiles per pass: 4 (64 bucket rows) at decode sizes,
-// 8 (128 rows) when experts see more rows, so that an expert's weights are
-// still read once.  One LDS buffer holds TB * 4 fragments.
+// TB = 16-row activation tiles per pass: 4 (64 bucket rows).  One LDS buffer
+// holds TB * 4 fragments.  (Passes of 128 rows existed: their register budget
+// leaves one workgroup per compute unit, and wherever buckets are that long the
+// tiled kernels measured faster.)
 constexpr int buf_bytes(int tb) { return tb * kStepsPerChunk * kFragBytes; }
 
 enum { kGateUp = 0, kDown = 1, kDownHalves = 2, kDownNarrow = 3 };
@@ -324,18 +325,12 @@ template <int MODE, int TB, int RT, bool ONCE>
 __device__ __forceinline__ void ffn_block_sized(int nt, const FfnArgs& a, const uint16_t* W0,
                                                 const uint16_t* W1, int n0, int r0, int row_end,
                                                 int shared_base, unsigned char* lds) {
-  if (TB <= 4) {
-    switch (nt) {
-      case 1: ffn_block<MODE, 1, TB, RT, ONCE>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
-      case 2: ffn_block<MODE, 2, TB, RT, ONCE>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
-      case 3: ffn_block<MODE, 3, TB, RT, ONCE>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
-      default: ffn_block<MODE, 4, TB, RT, ONCE>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
-    }
-  } else {
-    if (nt <= 2) ffn_block<MODE, 2, TB, RT, ONCE>(a, W0, W1, n0, r0, row_end, shared_base, lds);
-    else if (nt <= 4) ffn_block<MODE, 4, TB, RT, ONCE>(a, W0, W1, n0, r0, row_end, shared_base, lds);
-    else if (nt <= 6) ffn_block<MODE, 6, TB, RT, ONCE>(a, W0, W1, n0, r0, row_end, shared_base, lds);
-    else ffn_block<MODE, TB, TB, RT, ONCE>(a, W0, W1, n0, r0, row_end, shared_base, lds);
+  static_assert(TB == 4, "the variants below cover passes of up to four tiles");
+  switch (nt) {
+    case 1: ffn_block<MODE, 1, TB, RT, ONCE>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
+    case 2: ffn_block<MODE, 2, TB, RT, ONCE>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
+    case 3: ffn_block<MODE, 3, TB, RT, ONCE>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
+    default: ffn_block<MODE, 4, TB, RT, ONCE>(a, W0, W1, n0, r0, row_end, shared_base, lds); break;
   }
 }
 
@@ -2023,8 +2018,6 @@ __global__ __launch_bounds__(kThreads) void ffn_f32_kernel(F32Args a, ExpertTabl
 //               (down: one tile per wave, 64 weight rows per workgroup -- with
 //               128-row workgroups a fine-grained layer of some thirty active
 //               experts has barely more workgroups than the chip has slots)
-//   kStream128  the stream kernel, 128-row passes (an expert with up to 128
-//               rows still has its weights read once)
 //   kTile       the tiled kernel (persistent, both operands through LDS)
 //   kSplitK     down only: four waves split the contraction (32 rows per
 //               workgroup, activations straight from L2): keeps the chip full
@@ -2037,31 +2030,36 @@ __global__ __launch_bounds__(kThreads) void ffn_f32_kernel(F32Args a, ExpertTabl
 // so it also takes the gate/up phase of wide experts at decode sizes (their
 // many slabs balance over the persistent workgroups), and both phases from
 // about 24 rows per expert on.
-// MOE_TUNE_BLOCK=0|1|3 forces stream64 / stream128 / tile for both phases,
-// MOE_TUNE_GU=0|1|3 for gate/up only, MOE_TUNE_DOWN=lds|splitk|halves|tile
+// MOE_TUNE_BLOCK=0|3 forces stream / tile for both phases,
+// MOE_TUNE_GU=0|3 for gate/up only, MOE_TUNE_DOWN=lds|splitk|halves|tile
 // for down only (tuning builds only, see tune_env).
-enum Variant { kStream64 = 0, kStream128 = 1, kTile = 3, kSplitK = 4, kHalves = 5 };
+enum Variant { kStream64 = 0, kTile = 3, kSplitK = 4, kHalves = 5 };
 
 // The tiled kernel walks the contraction in steps of 64 and owns 64 / 128 rows.
 bool tile_kernel_fits(const moe_shape& s) { return s.H % 128 == 0 && s.F % 64 == 0; }
 
 static int forced_block() {
   static const char* env = tune_env("MOE_TUNE_BLOCK");
-  return (env && (env[0] == '0' || env[0] == '1' || env[0] == '3')) ? env[0] - '0' : -1;
+  return (env && (env[0] == '0' || env[0] == '3')) ? env[0] - '0' : -1;
 }
 
 static Variant rows_rule(const moe_shape& s) {
   const double rows = (double)s.T * s.k / s.E;   // expected rows per routed expert
   if (tile_kernel_fits(s) && (rows >= 24.0 || (s.S > 0 && s.T > 256))) return kTile;
-  if (rows > 48.0 || (s.S > 0 && s.T > 128)) return kStream128;
   return kStream64;
 }
 
 Variant gate_up_variant(const moe_shape& s, int n_groups) {
   static const char* env = tune_env("MOE_TUNE_GU");
-  if (env && (env[0] == '0' || env[0] == '1' || env[0] == '3')) return (Variant)(env[0] - '0');
+  if (env && (env[0] == '0' || env[0] == '3')) return (Variant)(env[0] - '0');
   if (forced_block() >= 0) return (Variant)forced_block();
   const Variant v = rows_rule(s);
+  // shared experts see every token: from about a hundred tokens their buckets
+  // (and the hot experts') would take the stream kernel two and more 64-row passes,
+  // each streaming the expert's weights again, while a block of the tiled kernel
+  // holds 256 rows (fine-grained layer with four shared experts, tiled against
+  // stream, us: 96 tokens 74.4 / 72.2, 128: 76.3 / 78.5, 160: 85 / 103, 256: 100 / 130)
+  if (v != kTile && tile_kernel_fits(s) && s.S > 0 && s.T > 96) return kTile;
   // wide experts: many slabs per expert, so the persistent workgroups get even
   // shares whatever number of experts turns out to be active.  Decided by the
   // layer's shape, not by how many experts this call lists: the streamed path
@@ -2124,10 +2122,6 @@ moe_status launch_ffn_gate_up(const moe_shape& s, const void* X, const int32_t* 
     const Variant v = gate_up_variant(s, groups.n);
     if (v == kTile && tile_kernel_fits(s)) {
       return launch_tile<kGateUp>(s, gu, tab, groups, stream, wide_form(s, 0));
-    } else if (v != kStream64) {
-      gu.heavy_first = s.S > 0 || s.T > 128;
-      hipLaunchKernelGGL((ffn_stream_kernel<kGateUp, 8, 1>), dim3(s.F / (kWaves * 16), groups.n, (s.T + 127) / 128),
-                         dim3(kThreads), 0, stream, gu, tab, groups);
     } else {
       gu.heavy_first = s.S > 0 || s.T > 64;
       hipLaunchKernelGGL((ffn_stream_kernel<kGateUp, 4, 1>), dim3(s.F / (kWaves * 16), groups.n, (s.T + 63) / 64),
@@ -2185,9 +2179,6 @@ moe_status launch_ffn_down(const moe_shape& s, const FfnScratch& scratch, const 
       else
         hipLaunchKernelGGL((ffn_down_splitk_kernel<2, kWaves>), dim3(s.H / kSplitRows, groups.n, tok_blocks),
                            dim3(kThreads), 0, stream, dn, tab, groups);
-    } else if (v != kStream64) {
-      hipLaunchKernelGGL((ffn_stream_kernel<kDown, 8, 1>), dim3(s.H / (kWaves * 32), groups.n, (s.T + 127) / 128),
-                         dim3(kThreads), 0, stream, dn, tab, groups);
     } else {
       hipLaunchKernelGGL((ffn_stream_kernel<kDownNarrow, 4, 1>), dim3(s.H / (kWaves * 16), groups.n, (s.T + 63) / 64),
                          dim3(kThreads), 0, stream, dn, tab, groups);
@@ -2236,8 +2227,7 @@ const char* ffn_kernel_name(const moe_shape& s, int phase, int n_groups) {
       return phase == 0 ? "ffn_tile_kernel<gate/up>" : "ffn_tile_kernel<down>";
     case kSplitK: return "ffn_down_splitk_kernel";
     case kHalves: return "ffn_stream_kernel<down, halved contraction>";
-    case kStream64: return phase == 0 ? "ffn_stream_kernel<gate/up, 64 rows>" : "ffn_stream_kernel<down, 64 rows>";
-    default: return phase == 0 ? "ffn_stream_kernel<gate/up, 128 rows>" : "ffn_stream_kernel<down, 128 rows>";
+    default: return phase == 0 ? "ffn_stream_kernel<gate/up, 64 rows>" : "ffn_stream_kernel<down, 64 rows>";
   }
 }
 

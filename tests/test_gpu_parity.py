@@ -72,7 +72,8 @@ SMALL = [
     _small("s_bf16_route_deep", T=20, E=60, k=4, H=4224, F=128),
     _small("s_bf16_route_mfma_8waves", T=260, E=128, k=8, H=2176, F=128),
     _small("s_bf16_route_fused_long", T=6, E=8, k=2, H=4224, F=128),
-    # FFN kernel choices not reached above: halved-contraction down, 128-row stream passes,
+    # FFN kernel choices not reached above: halved-contraction down, shared experts over 200 tokens
+    # (tiled gate/up, several 64-row passes of the one-tile down form),
     # the tiled kernel as the gate/up kernel of wide experts at decode sizes
     _small("s_bf16_halves", T=40, E=4, k=2, H=256, F=512),
     _small("s_bf16_128row_passes", T=200, E=60, k=4, S=1, H=128, F=256, bias="zipf", bias_scale=1.1),
@@ -618,8 +619,7 @@ def test_small_configs_reach_every_ffn_kernel(B):
             "ffn_tile_small_kernel<down>", "ffn_wide_kernel<gate/up>",
             "ffn_wide_kernel<down>", "ffn_down_splitk_kernel",
             "ffn_stream_kernel<down, halved contraction>", "ffn_stream_kernel<gate/up, 64 rows>",
-            "ffn_stream_kernel<down, 64 rows>", "ffn_stream_kernel<gate/up, 128 rows>",
-            "ffn_stream_kernel<down, 128 rows>", "ffn_f32_kernel<gate/up>", "ffn_f32_kernel<down>"}
+            "ffn_stream_kernel<down, 64 rows>", "ffn_f32_kernel<gate/up>", "ffn_f32_kernel<down>"}
     assert want <= seen, want - seen
 
 

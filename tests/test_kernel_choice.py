@@ -36,8 +36,14 @@ def test_mixtral_decode_sizes(B):
 
 
 def test_fine_grained_and_prefill(B):
+    # shared experts over about a hundred tokens: gate/up in 256-row blocks of the tiled
+    # kernel (one pass over their weights), down in the stream kernel's 64-column form
     assert _names(B, get_config("c3_finegrained")) == (
-        "ffn_stream_kernel<gate/up, 64 rows>", "ffn_stream_kernel<down, 64 rows>")
+        "ffn_tile_kernel<gate/up>", "ffn_stream_kernel<down, 64 rows>")
+    c3 = get_config("c3_finegrained")
+    assert _names(B, c3, 96) == ("ffn_stream_kernel<gate/up, 64 rows>", "ffn_stream_kernel<down, 64 rows>")
+    assert _names(B, c3, 256) == ("ffn_tile_kernel<gate/up>", "ffn_stream_kernel<down, 64 rows>")
+    assert _names(B, c3, 257) == ("ffn_wide_kernel<gate/up>", "ffn_wide_kernel<down>")
     assert _names(B, get_config("c4_dsv2lite_prefill")) == (
         "ffn_wide_kernel<gate/up>", "ffn_wide_kernel<down>")
     # many experts with a few rows each: enough workgroups without split-K
