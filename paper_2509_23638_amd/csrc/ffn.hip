@@ -25,6 +25,7 @@
 // of a row block), for the small full-precision configuration.
 #include "common.h"
 
+#include <math.h>
 #include <stdlib.h>
 
 #include <algorithm>
@@ -2082,13 +2083,16 @@ Variant down_variant(const moe_shape& s) {
   const Variant v = rows_rule(s);
   if (v != kStream64) return v;
   const double rows = (double)s.T * s.k / s.E;
-  // wide experts at decode sizes: from about a dozen rows per expert the small
-  // tiled kernel's ring streams the down projection faster than the halved
-  // stream kernel (Mixtral shape: 146 against 150 us at 64 tokens, 145 against
-  // 150 at 48, equal at 32, slower below)
-  if (tile_kernel_fits(s) && s.T <= 64 && rows >= 12.0 && s.H / 128 >= 32 &&
-      (long)(s.E + s.S) * (s.H / 128) >= 256)
-    return kTile;
+  // wide outputs: the tiled kernel's ring streams the down projection faster
+  // than the halved stream kernel and split-K as soon as its items -- (active
+  // expert, 128 output columns) -- about fill the chip.  The experts a batch
+  // activates are not known here; their expected number under uniform routing
+  // stands in.  Mixtral shape, down phase in us, tiled against the rest: 10
+  // tokens 125.8 / 126.0, 12: 128.6 / 132.6, 24: 138.5 / 144.1, 32: 138.9 /
+  // 144.9, 48: 139.5 / 146.5, 65: 141.2 / 157.6, 80: 143.4 / 163.3; below (8
+  // tokens, seven active experts) split-K wins, 122.2 against 125.5.
+  const double active = s.E * (1.0 - pow(1.0 - 1.0 / s.E, (double)s.T * s.k)) + s.S;
+  if (tile_kernel_fits(s) && s.H / 128 >= 32 && active * (s.H / 128) >= 240.0) return kTile;
   // split-K exists to fill the chip when few experts are active; with many
   // experts the halved stream kernel already has thousands of workgroups and
   // measured 9 % faster (128 experts of 2048 x 768, four rows each)

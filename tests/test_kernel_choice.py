@@ -27,7 +27,11 @@ def test_mixtral_decode_sizes(B):
     cfg = get_config("c2_mixtral")
     # wide experts: the persistent tiled kernel streams gate/up at every decode batch
     assert _names(B, cfg, 64) == ("ffn_tile_small_kernel<gate/up>", "ffn_tile_small_kernel<down>")
-    assert _names(B, cfg, 32) == ("ffn_tile_small_kernel<gate/up>", "ffn_stream_kernel<down, halved contraction>")
+    # the down projection too, once its (active expert, 128 columns) items about fill the chip
+    assert _names(B, cfg, 32) == ("ffn_tile_small_kernel<gate/up>", "ffn_tile_small_kernel<down>")
+    assert _names(B, cfg, 12) == ("ffn_tile_small_kernel<gate/up>", "ffn_tile_small_kernel<down>")
+    assert _names(B, cfg, 10) == ("ffn_tile_small_kernel<gate/up>", "ffn_down_splitk_kernel")
+    assert _names(B, cfg, 65) == ("ffn_tile_kernel<gate/up>", "ffn_tile_kernel<down>")
     assert _names(B, cfg, 1) == ("ffn_tile_small_kernel<gate/up>", "ffn_down_splitk_kernel")
     assert _names(B, cfg, 8) == ("ffn_tile_small_kernel<gate/up>", "ffn_down_splitk_kernel")
     # from about 24 rows per expert both phases are tiled, from 96 in the eight-wave form
