@@ -1709,7 +1709,7 @@ bool wide_form(const moe_shape& s, int phase) {
   if (N % (phase == 0 ? kWideSlabGateUp : kWideSlabDown) != 0) return false;
   if (K / kTileK < kWideMinStages || act_rows * K * 2 >= (1ll << 31)) return false;
   static const char* env = tune_env("MOE_TUNE_WIDE");
-  if (env && (env[0] == '0' || env[0] == '1')) return env[0] == '1';
+  if (env && (env[0] == '0' || env[0] == '1')) return (env[1] ? env[phase] : env[0]) == '1';   // "10": gate/up only
   const double rows = (double)s.T * s.k / s.E;
   return rows >= 96.0 || (s.S > 0 && s.T > 256);
 }
