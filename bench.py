@@ -140,6 +140,22 @@ def hbm_probe(torch, B):
         e1.record()
         torch.cuda.synchronize()
         out[name + "_GBps"] = nbytes * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    # the tiled kernels' stage loop on its own: 16 KiB of weights per stage and compute unit out of HBM,
+    # beside 0 .. 32 KiB of token rows out of L2 (what bytes that hit in L2 cost an HBM-bound stream)
+    stages = 448
+    tokens = torch.zeros(2 << 20, dtype=torch.uint8, device="cuda")
+    wbytes = 256 * stages * 16384
+    for n in range(5):
+        for _ in range(2):
+            B.moe_probe_stage(big[:wbytes], tokens, n, stages)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            B.moe_probe_stage(big[:wbytes], tokens, n, stages)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / 5
+        out[f"stage_loop_{8 * n}KiB_tokens"] = {"us_per_stage": us / stages, "weights_GBps": wbytes / us / 1e3}
     return out
 
 

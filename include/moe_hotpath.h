@@ -374,6 +374,17 @@ moe_status moe_probe_read(const void* src, size_t bytes, void* sink4, void* stre
  * weight tiles that are read once), eight 1 KiB loads in flight per wavefront
  * over 8 KiB in a row. */
 moe_status moe_probe_read_nt(const void* src, size_t bytes, void* sink4, void* stream);
+/* The stage loop of the tiled FFN kernels with nothing multiplied: 256
+ * workgroups of eight waves, each streaming `stages` x 16 KiB of its own out of
+ * `weights` (device, at least 256 x stages x 16 KiB, non-temporal loads) while
+ * it fetches token_fetches x 8 KiB per stage (0..4; 8 rows x 128 B per
+ * instruction) out of `tokens` (device, at least 2 MiB: 256 rows of 8 KiB, which
+ * stay in L2), direct-to-LDS into a ring with two stages in flight.  Timed by
+ * the caller, it shows how far bytes that hit in L2 slow an HBM-bound weight
+ * stream down.  Nothing is written to global memory.  MOE_ERR_INVALID_ARG for
+ * buffers that are too small or arguments out of range. */
+moe_status moe_probe_stage(const void* weights, size_t weight_bytes, const void* tokens,
+                           size_t token_bytes, int32_t token_fetches, int32_t stages, void* stream);
 
 /* Which kernel the grouped FFN launches for a shape (measurement aid for
  * reports): phase 0 = gate/up, 1 = down.  The choice depends on the shape

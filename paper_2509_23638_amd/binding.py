@@ -128,6 +128,7 @@ _lib.moe_phase_times_get.argtypes = [_P, C.POINTER(moe_phase_times), C.c_int32]
 _lib.moe_probe_copy.argtypes = [_P, _P, C.c_size_t, _P]
 _lib.moe_probe_read.argtypes = [_P, C.c_size_t, _P, _P]
 _lib.moe_probe_read_nt.argtypes = [_P, C.c_size_t, _P, _P]
+_lib.moe_probe_stage.argtypes = [_P, C.c_size_t, _P, C.c_size_t, C.c_int32, C.c_int32, _P]
 _lib.moe_set_option.argtypes = [_P, C.c_int32, C.c_int64]
 _lib.moe_pack_weights.argtypes = [_P, _P, C.c_int32, C.c_int32, _P]
 _lib.moe_rmsnorm.argtypes = [_SH, _P, _P, C.c_float, _P]
@@ -146,15 +147,15 @@ for _n in ("moe_counter_add", "moe_hot_table", "moe_predict_counts", "moe_presch
            "moe_route", "moe_permute", "moe_grouped_ffn", "moe_combine", "moe_create",
            "moe_destroy", "moe_layer_forward", "moe_layer_forward_static", "moe_stream_totals_get",
            "moe_workspace_views", "moe_phase_timing", "moe_phase_times_get", "moe_probe_copy", "moe_probe_read",
-           "moe_probe_read_nt", "moe_rmsnorm", "moe_set_option", "moe_pack_weights", "moe_prefetch",
-           "moe_layer_counts"):
+           "moe_probe_read_nt", "moe_probe_stage", "moe_rmsnorm", "moe_set_option", "moe_pack_weights",
+           "moe_prefetch", "moe_layer_counts"):
     getattr(_lib, _n).restype = C.c_int32
 
 EXPORTS = ["moe_version", "moe_last_error", "moe_workspace_bytes", "moe_route", "moe_permute",
            "moe_grouped_ffn", "moe_combine", "moe_create", "moe_destroy", "moe_layer_forward",
            "moe_stream_totals_get", "moe_workspace_views", "moe_phase_timing",
            "moe_phase_times_get", "moe_probe_copy", "moe_probe_read", "moe_probe_read_nt",
-           "moe_rmsnorm", "moe_set_option", "moe_pack_weights",
+           "moe_probe_stage", "moe_rmsnorm", "moe_set_option", "moe_pack_weights",
            "moe_counter_add", "moe_hot_table", "moe_predict_counts", "moe_presched",
            "moe_ffn_kernel_name", "moe_layer_forward_static", "moe_static_workspace_bytes",
            "moe_pending_experts", "moe_prefetch_hottest", "moe_prefetch", "moe_layer_counts",
@@ -468,6 +469,12 @@ def moe_probe_read(src: torch.Tensor, sink: torch.Tensor, stream=None):
 def moe_probe_read_nt(src: torch.Tensor, sink: torch.Tensor, stream=None):
     n = src.numel() * src.element_size()
     _check(_lib.moe_probe_read_nt(_ptr(src, "src"), n, _ptr(sink, "sink", None, 1), _stream(stream)))
+
+
+def moe_probe_stage(weights: torch.Tensor, tokens: torch.Tensor, token_fetches: int, stages: int, stream=None):
+    _check(_lib.moe_probe_stage(_ptr(weights, "weights"), weights.numel() * weights.element_size(),
+                                _ptr(tokens, "tokens"), tokens.numel() * tokens.element_size(),
+                                int(token_fetches), int(stages), _stream(stream)))
 
 
 def moe_workspace_views(shape, workspace: torch.Tensor) -> dict:

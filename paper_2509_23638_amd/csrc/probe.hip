@@ -1,5 +1,6 @@
 // Measurement aids: a plain streaming copy and a plain streaming read (with and
-// without the non-temporal hint), 16 bytes per lane.  They give the achievable HBM rate of the box the roofline
+// without the non-temporal hint), 16 bytes per lane, and the stage loop of the
+// tiled FFN kernels on its own.  They give the achievable HBM rate of the box the roofline
 // fraction is quoted next to, and a dispatch of known size against which
 // hardware byte counters can be scaled.
 #include "common.h"
@@ -53,6 +54,70 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const uint4* __restrict
   if (acc == 0x9e3779b9u) sink[0] = acc;
 }
 
+// The stage loop of the tiled FFN kernels and nothing else: what a compute unit
+// can take in while it streams weights.  One workgroup of eight waves per
+// compute unit; per stage it fetches 16 KiB of "weights" (its own stream through
+// `w`, one KiB per instruction, non-temporal) and NTOK x 8 KiB of "token rows"
+// (8 rows x 128 B per instruction out of a 2 MiB matrix of 256 rows that stays in
+// L2) with the direct-to-LDS load, into a ring of three buffers with two stages
+// in flight, behind a counted vmcnt wait and a bare barrier.  Nothing is
+// multiplied.  Loads complete in order, so "at most one stage's loads
+// outstanding" says the stage at hand has landed.
+constexpr int kStageWaves = 8;
+constexpr int kStageWorkgroups = 256;
+constexpr size_t kStageTokenBytes = 256 * 8192;
+
+template <int NTOK>
+__global__ __launch_bounds__(kStageWaves * 64, 1) void probe_stage_kernel(const unsigned char* __restrict__ w,
+                                                                          size_t w_stride,
+                                                                          const unsigned char* __restrict__ tok,
+                                                                          int stages) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char ring[];
+  constexpr int PER = 2 + NTOK;                       // loads per wave and stage
+  constexpr int SLOT = PER * kStageWaves * 1024;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const unsigned char* wp = w + (size_t)blockIdx.x * w_stride + (size_t)wave * 2048 + lane * 16;
+  const unsigned char* tp[NTOK > 0 ? NTOK : 1];
+#pragma unroll
+  for (int q = 0; q < NTOK; ++q) {
+    const int grp = (wave + 8 * q + blockIdx.x) & 31;   // 8 of the 256 rows
+    tp[q] = tok + (size_t)(grp * 8 + (lane >> 3)) * 8192 + (lane & 7) * 16;
+  }
+  auto issue = [&](int st) {
+    unsigned char* base = ring + (st % 3) * SLOT + wave * PER * 1024;
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(wp + (size_t)st * (kStageWaves * 2048) + q * 1024),
+          (__attribute__((address_space(3))) void*)(base + q * 1024), 16, 0, 2);
+#pragma unroll
+    for (int q = 0; q < NTOK; ++q)
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(tp[q] + (st & 63) * 128),
+          (__attribute__((address_space(3))) void*)(base + (2 + q) * 1024), 16, 0, 0);
+  };
+  issue(0);
+  issue(1);
+  for (int st = 0; st < stages; ++st) {
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(PER) : "memory");
+    issue(st + 2 < stages ? st + 2 : stages - 1);     // the tail re-reads the last stage: equal counts
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+template <int NTOK>
+moe_status launch_probe_stage(const void* w, size_t w_stride, const void* tok, int stages, hipStream_t stream) {
+  const int lds = 3 * (2 + NTOK) * kStageWaves * 1024;
+  MOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&probe_stage_kernel<NTOK>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+  hipLaunchKernelGGL(probe_stage_kernel<NTOK>, dim3(kStageWorkgroups), dim3(kStageWaves * 64), lds, stream,
+                     static_cast<const unsigned char*>(w), w_stride, static_cast<const unsigned char*>(tok),
+                     stages);
+  MOE_HIP(hipGetLastError());
+  return MOE_OK;
+}
+
 template <bool NT>
 moe_status launch_probe_read(const void* src, size_t bytes, void* sink4, void* stream) {
   const size_t n = bytes / 16;
@@ -91,4 +156,25 @@ extern "C" moe_status moe_probe_read_nt(const void* src, size_t bytes, void* sin
   MOE_REQUIRE(src && sink4 && bytes % 16 == 0,
               "moe_probe_read_nt: NULL pointer or size not a multiple of 16");
   return moe::launch_probe_read<true>(src, bytes, sink4, stream);
+}
+
+extern "C" moe_status moe_probe_stage(const void* weights, size_t weight_bytes, const void* tokens,
+                                      size_t token_bytes, int32_t token_fetches, int32_t stages,
+                                      void* stream) {
+  MOE_REQUIRE(weights && tokens, "moe_probe_stage: NULL pointer argument");
+  MOE_REQUIRE(token_fetches >= 0 && token_fetches <= 4, "moe_probe_stage: token_fetches must be 0..4");
+  MOE_REQUIRE(stages >= 2 && stages <= (1 << 20), "moe_probe_stage: stages must be 2..2^20");
+  // every workgroup walks its own stages x 16 KiB; the token matrix is 256 rows of 8 KiB
+  const size_t w_stride = (size_t)stages * moe::kStageWaves * 2048;
+  MOE_REQUIRE(weight_bytes >= w_stride * moe::kStageWorkgroups,
+              "moe_probe_stage: weights must hold 256 x stages x 16 KiB");
+  MOE_REQUIRE(token_bytes >= moe::kStageTokenBytes, "moe_probe_stage: tokens must hold 2 MiB");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  switch (token_fetches) {
+    case 0: return moe::launch_probe_stage<0>(weights, w_stride, tokens, stages, s);
+    case 1: return moe::launch_probe_stage<1>(weights, w_stride, tokens, stages, s);
+    case 2: return moe::launch_probe_stage<2>(weights, w_stride, tokens, stages, s);
+    case 3: return moe::launch_probe_stage<3>(weights, w_stride, tokens, stages, s);
+    default: return moe::launch_probe_stage<4>(weights, w_stride, tokens, stages, s);
+  }
 }

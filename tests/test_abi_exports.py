@@ -61,6 +61,25 @@ def test_host_side_argument_checks(lib):
     assert B.moe_version().startswith("moe_hotpath")
 
 
+def test_stage_probe_rejects_what_it_could_not_run_in_bounds(lib):
+    """The stage-loop probe sizes its accesses from its arguments: buffers that are too small or
+    counts out of range are refused on the host, before anything is launched."""
+    f = lib.moe_probe_stage
+    f.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32,
+                  ctypes.c_int32, ctypes.c_void_p]
+    f.restype = ctypes.c_int32
+    fake = 0x1000   # never dereferenced: every call below fails its checks
+    stages = 8
+    need = 256 * stages * 16384
+    assert f(None, need, fake, 2 << 20, 1, stages, None) == -1
+    assert f(fake, need, None, 2 << 20, 1, stages, None) == -1
+    assert f(fake, need - 1, fake, 2 << 20, 1, stages, None) == -1     # weights one byte short
+    assert f(fake, need, fake, (2 << 20) - 1, 1, stages, None) == -1   # token matrix short
+    assert f(fake, need, fake, 2 << 20, 5, stages, None) == -1
+    assert f(fake, need, fake, 2 << 20, -1, stages, None) == -1
+    assert f(fake, need, fake, 2 << 20, 1, 1, None) == -1
+
+
 def test_harness_prefetch_mask_matches_oracle_reading(lib):
     """The harness-side predictor stand-in and the oracle's statement of the
     same reading are written separately; they must pick the same experts."""

@@ -885,3 +885,18 @@ def test_phase_markers_count_the_layers_they_mark_and_leave_results_alone(B):
     for mode in (1, 2, 3):
         assert np.array_equal(outs[mode], outs[0])
     ctx.close()
+
+
+@pytest.mark.gpu
+def test_stage_probe_runs_and_leaves_its_inputs_alone(B):
+    """The measurement aid reads its two buffers and writes nothing to global memory."""
+    stages = 16
+    w = torch.arange(256 * stages * 16384 // 4, dtype=torch.int32, device="cuda")
+    tok = torch.arange((2 << 20) // 4, dtype=torch.int32, device="cuda")
+    w0, t0 = w.clone(), tok.clone()
+    for n in range(5):
+        B.moe_probe_stage(w, tok, n, stages)
+    torch.cuda.synchronize()
+    assert torch.equal(w, w0) and torch.equal(tok, t0)
+    with pytest.raises(B.MoEError):
+        B.moe_probe_stage(w[:-1], tok, 1, stages)
