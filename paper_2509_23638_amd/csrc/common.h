@@ -76,6 +76,10 @@ struct FfnScratch {
 // internal launchers (each enqueues on `stream`, returns a status)
 moe_status launch_route(const moe_shape& s, const void* X, const void* Wr, const float* bias,
                         int32_t* topk_idx, float* topk_w, double* logits_out, hipStream_t stream);
+moe_status launch_route_bucket(const moe_shape& s, const void* X, const void* Wr, const float* bias,
+                               int32_t* topk_idx, float* topk_w, double* logits, int32_t* count,
+                               int32_t* offset, int32_t* perm, int32_t* inv_perm, hipStream_t stream,
+                               bool* bucketed);
 moe_status launch_permute(const moe_shape& s, const int32_t* topk_idx, int32_t* count,
                           int32_t* offset, int32_t* perm, int32_t* inv_perm, hipStream_t stream);
 moe_status launch_grouped_ffn(const moe_shape& s, const void* X, const int32_t* perm,

@@ -410,11 +410,13 @@ extern "C" moe_status moe_layer_forward(moe_ctx* c, const moe_shape* shape,
   } while (0)
   if (timed) c->phase_kinds.push_back(timed);
   PHASE_MARK(0);
-  st = launch_route(s, X, layer->Wr, layer->bias, topk_idx, topk_w,
-                    reinterpret_cast<double*>(w + L.logits), stream);
+  bool bucketed = false;   // a batch of one token: the selecting launch buckets as well
+  st = launch_route_bucket(s, X, layer->Wr, layer->bias, topk_idx, topk_w,
+                           reinterpret_cast<double*>(w + L.logits), count, offset, perm, inv_perm, stream,
+                           &bucketed);
   if (st != MOE_OK) return st;
   PHASE_MARK(1);
-  st = launch_permute(s, topk_idx, count, offset, perm, inv_perm, stream);
+  if (!bucketed) st = launch_permute(s, topk_idx, count, offset, perm, inv_perm, stream);
   if (st != MOE_OK) return st;
   if (c->export_counts) {
     // for a scheduler on the host: the counts travel while the FFN runs, and
@@ -733,10 +735,12 @@ extern "C" moe_status moe_layer_forward_static(const moe_shape* shape, const moe
   const bool y_bf16 = layer_y_bf16(s);   // as in moe_layer_forward: the two must agree bit for bit
   // nothing in the workspace has to start at zero: every kernel below writes
   // what the next one reads (the previous call's contents are simply overwritten)
-  st = launch_route(s, X, layer->Wr, layer->bias, topk_idx, topk_w,
-                    reinterpret_cast<double*>(w + L.logits), stream);
+  bool bucketed = false;
+  st = launch_route_bucket(s, X, layer->Wr, layer->bias, topk_idx, topk_w,
+                           reinterpret_cast<double*>(w + L.logits), count, offset, perm, inv_perm, stream,
+                           &bucketed);
   if (st != MOE_OK) return st;
-  st = launch_permute(s, topk_idx, count, offset, perm, inv_perm, stream);
+  if (!bucketed) st = launch_permute(s, topk_idx, count, offset, perm, inv_perm, stream);
   if (st != MOE_OK) return st;
   st = launch_ffn_gate_up(s, X, perm, offset, tab, groups, h, stream);
   if (st != MOE_OK) return st;

@@ -123,9 +123,17 @@ __device__ __forceinline__ double readlane_f64(double v, int lane_uniform) {
 // lanes share the leading word -- a wave-uniform, rarely taken branch.  The
 // r-th winner's logit and index are parked in lane r, so the weights need one
 // expf per lane and no LDS.  Every lane of the wave must call this.
+// Where a launch of ONE token also leaves its buckets (count [E], offset
+// [E+1], perm [k], inv_perm [k], as permute_kernel writes them); all NULL
+// otherwise.
+struct OneTokenBuckets {
+  int32_t *count, *offset, *perm, *inv_perm;
+};
+
 __device__ __forceinline__ void select_topk(double c0, double c1, int E, int k, bool store, size_t t,
                                             int lane, int32_t* __restrict__ topk_idx,
-                                            float* __restrict__ topk_w) {
+                                            float* __restrict__ topk_w,
+                                            OneTokenBuckets one = OneTokenBuckets{nullptr, nullptr, nullptr, nullptr}) {
   const int e0 = lane, e1 = lane + MOE_WAVE;
   uint64_t key0 = e0 < E ? sortable_key(c0) : 0ull;
   uint64_t key1 = e1 < E ? sortable_key(c1) : 0ull;
@@ -167,6 +175,36 @@ __device__ __forceinline__ void select_topk(double c0, double c1, int E, int k, 
   if (store && lane < k) {
     topk_idx[t * k + lane] = sel_i;
     topk_w[t * k + lane] = ex / sum;
+  }
+  // A batch of one token: its k assignments are the whole list, so the buckets
+  // are known here and the bucketing launch is saved (a tenth of a one-token
+  // layer's dependent launches).  Lane l answers for experts l and l + 64 and,
+  // if l < k, for assignment l: count = assignments naming the expert, offset =
+  // assignments naming a lower one, position = assignments that sort before
+  // this one (lower expert, or the same expert earlier in the list: stable).
+  if (one.count != nullptr) {
+    int n0 = 0, n1 = 0, less0 = 0, less1 = 0, pos = 0;
+    for (int r = 0; r < k; ++r) {
+      const int32_t v = __builtin_amdgcn_readlane(sel_i, r);
+      n0 += v == e0;
+      n1 += v == e1;
+      less0 += v < e0;
+      less1 += v < e1;
+      pos += v < sel_i || (v == sel_i && r < lane);
+    }
+    if (e0 < E) {
+      one.count[e0] = n0;
+      one.offset[e0] = less0;
+    }
+    if (e1 < E) {
+      one.count[e1] = n1;
+      one.offset[e1] = less1;
+    }
+    if (lane == 0) one.offset[E] = k;
+    if (lane < k) {
+      one.perm[pos] = lane;
+      one.inv_perm[lane] = pos;
+    }
   }
 }
 
@@ -225,7 +263,7 @@ template <typename ST, int EPW, int TPL, int RT, int KS, int UNR, bool PIPE, boo
 __global__ __launch_bounds__(KS* MOE_WAVE) void route_logits_kernel(
     const void* __restrict__ X, const void* __restrict__ Wr, const float* __restrict__ bias,
     double* __restrict__ logits, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, int T,
-    int H, int E, int k) {
+    int H, int E, int k, OneTokenBuckets one) {
   constexpr int TPW = RT * TPL;                      // tokens per workgroup
   constexpr int NP = KS * (4 / RT);                  // partial sums per (expert, token)
   constexpr int PS = RT == 4 ? 128 : 512;            // positions per step
@@ -297,7 +335,7 @@ __global__ __launch_bounds__(KS* MOE_WAVE) void route_logits_kernel(
     if (wave < TPW) {                                // whole wavefronts; no barrier below
       const bool store = t0 + wave < T;
       const double c0 = lane < EPW ? s_logit[wave][lane] : 0.0;
-      select_topk(c0, 0.0, E, k, store, (size_t)min(t0 + wave, T - 1), lane, topk_idx, topk_w);
+      select_topk(c0, 0.0, E, k, store, (size_t)min(t0 + wave, T - 1), lane, topk_idx, topk_w, one);
     }
   }
 }
@@ -400,7 +438,7 @@ constexpr long kMfmaTiles = 128;   // 16 x 16 logit tiles from which the matrix-
 // wavefront per token.
 __global__ __launch_bounds__(kSelectWaves* MOE_WAVE) void route_select_kernel(
     const double* __restrict__ logits, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
-    int T, int E, int k) {
+    int T, int E, int k, OneTokenBuckets one) {
   const int lane = threadIdx.x & (MOE_WAVE - 1);
   const int tk = threadIdx.x / MOE_WAVE;
   const int t = min(blockIdx.x * kSelectWaves + tk, T - 1);
@@ -408,18 +446,19 @@ __global__ __launch_bounds__(kSelectWaves* MOE_WAVE) void route_select_kernel(
   const int e0 = lane, e1 = lane + MOE_WAVE;
   const double c0 = e0 < E ? logits[(size_t)t * E + e0] : 0.0;
   const double c1 = e1 < E ? logits[(size_t)t * E + e1] : 0.0;
-  select_topk(c0, c1, E, k, store, (size_t)t, lane, topk_idx, topk_w);
+  select_topk(c0, c1, E, k, store, (size_t)t, lane, topk_idx, topk_w, store ? one : OneTokenBuckets{});
 }
 
 // Returns true when the launch also selected (fused form).
 template <typename ST>
 bool launch_logits(const moe_shape& s, const void* X, const void* Wr, const float* bias,
-                   double* logits, int32_t* topk_idx, float* topk_w, hipStream_t stream) {
+                   double* logits, int32_t* topk_idx, float* topk_w, hipStream_t stream,
+                   OneTokenBuckets one) {
 #define LOGITS_LAUNCH(EPW, TPL, RT, KS, UNR, PIPE, FUSE)                                        \
   hipLaunchKernelGGL((route_logits_kernel<ST, EPW, TPL, RT, KS, UNR, PIPE, FUSE>),              \
                      dim3((s.T + RT * TPL - 1) / (RT * TPL), (s.E + EPW - 1) / EPW),            \
                      dim3(KS * MOE_WAVE), 0, stream, X, Wr, bias, logits, topk_idx, topk_w,     \
-                     s.T, s.H, s.E, s.k)
+                     s.T, s.H, s.E, s.k, one)
   constexpr bool wide = sizeof(ST) == 4;   // float32 rows take twice the registers per fetch
   auto blocks = [&](int epw, int tpw) {
     return (long)((s.T + tpw - 1) / tpw) * ((s.E + epw - 1) / epw);
@@ -477,20 +516,38 @@ bool launch_logits(const moe_shape& s, const void* X, const void* Wr, const floa
 }  // namespace
 
 // `logits` [T,E] float64 is required: an output the caller wants, or scratch.
-moe_status launch_route(const moe_shape& s, const void* X, const void* Wr, const float* bias,
-                        int32_t* topk_idx, float* topk_w, double* logits, hipStream_t stream) {
+// With `one` set (a batch of one token) the selecting launch also writes the buckets.
+static moe_status route_impl(const moe_shape& s, const void* X, const void* Wr, const float* bias,
+                             int32_t* topk_idx, float* topk_w, double* logits, hipStream_t stream,
+                             OneTokenBuckets one) {
   if (s.T == 0) return MOE_OK;
   const bool selected = s.dtype == MOE_BF16
-      ? launch_logits<uint16_t>(s, X, Wr, bias, logits, topk_idx, topk_w, stream)
-      : launch_logits<float>(s, X, Wr, bias, logits, topk_idx, topk_w, stream);
+      ? launch_logits<uint16_t>(s, X, Wr, bias, logits, topk_idx, topk_w, stream, one)
+      : launch_logits<float>(s, X, Wr, bias, logits, topk_idx, topk_w, stream, one);
   MOE_HIP(hipGetLastError());
   if (!selected) {
     hipLaunchKernelGGL(route_select_kernel, dim3((s.T + kSelectWaves - 1) / kSelectWaves),
                        dim3(kSelectWaves * MOE_WAVE), 0, stream, logits, topk_idx, topk_w, s.T, s.E,
-                       s.k);
+                       s.k, one);
     MOE_HIP(hipGetLastError());
   }
   return MOE_OK;
+}
+
+moe_status launch_route(const moe_shape& s, const void* X, const void* Wr, const float* bias,
+                        int32_t* topk_idx, float* topk_w, double* logits, hipStream_t stream) {
+  return route_impl(s, X, Wr, bias, topk_idx, topk_w, logits, stream, OneTokenBuckets{});
+}
+
+// Routing for the whole block: for a batch of one token the selecting launch
+// buckets as well (`bucketed` says so), else the caller runs launch_permute.
+moe_status launch_route_bucket(const moe_shape& s, const void* X, const void* Wr, const float* bias,
+                               int32_t* topk_idx, float* topk_w, double* logits, int32_t* count,
+                               int32_t* offset, int32_t* perm, int32_t* inv_perm, hipStream_t stream,
+                               bool* bucketed) {
+  *bucketed = s.T == 1 && s.k <= MOE_WAVE;
+  const OneTokenBuckets one = *bucketed ? OneTokenBuckets{count, offset, perm, inv_perm} : OneTokenBuckets{};
+  return route_impl(s, X, Wr, bias, topk_idx, topk_w, logits, stream, one);
 }
 
 }  // namespace moe

@@ -85,12 +85,17 @@ extern "C" moe_status moe_predict_counts(const moe_shape* shape, const void* X, 
   int32_t* idx = reinterpret_cast<int32_t*>(base + w.topk_idx);
   float* wts = reinterpret_cast<float*>(base + w.topk_w);
   int32_t* count = reinterpret_cast<int32_t*>(base + w.count);
-  st = moe::launch_route(*shape, X, Wr_next, bias_next, idx, wts,
-                         reinterpret_cast<double*>(base + w.logits), s);
+  bool bucketed = false;
+  st = moe::launch_route_bucket(*shape, X, Wr_next, bias_next, idx, wts,
+                                reinterpret_cast<double*>(base + w.logits), count,
+                                reinterpret_cast<int32_t*>(base + w.offset),
+                                reinterpret_cast<int32_t*>(base + w.perm),
+                                reinterpret_cast<int32_t*>(base + w.inv_perm), s, &bucketed);
   if (st != MOE_OK) return st;
-  st = moe::launch_permute(*shape, idx, count, reinterpret_cast<int32_t*>(base + w.offset),
-                           reinterpret_cast<int32_t*>(base + w.perm),
-                           reinterpret_cast<int32_t*>(base + w.inv_perm), s);
+  if (!bucketed)
+    st = moe::launch_permute(*shape, idx, count, reinterpret_cast<int32_t*>(base + w.offset),
+                             reinterpret_cast<int32_t*>(base + w.perm),
+                             reinterpret_cast<int32_t*>(base + w.inv_perm), s);
   if (st != MOE_OK) return st;
   MOE_HIP(hipMemcpyAsync(pred_count, count, shape->E * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
   return MOE_OK;

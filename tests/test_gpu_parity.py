@@ -900,3 +900,33 @@ def test_stage_probe_runs_and_leaves_its_inputs_alone(B):
     assert torch.equal(w, w0) and torch.equal(tok, t0)
     with pytest.raises(B.MoEError):
         B.moe_probe_stage(w[:-1], tok, 1, stages)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("E,k,S", [(8, 2, 0), (8, 8, 0), (60, 4, 2), (128, 8, 0), (128, 16, 8), (1, 1, 0)])
+def test_one_token_buckets_come_from_the_selecting_launch(B, E, k, S):
+    """A batch of one token is bucketed by the launch that selects (no bucketing launch):
+    count, offset, perm and inv_perm must be what the oracle's stable bucketing gives."""
+    cfg = _small(f"one_{E}_{k}_{S}", T=1, E=E, k=k, S=S, H=256, F=128, bias="normal")
+    L = make_layer(cfg)
+    sh = _shape(B, cfg, 1)
+    ctx = B.Context(sh)
+    Wg, Wu, Wd = _experts_dev(B, L, "row_major")
+    layer = B.make_layer_desc(sh, to_dev(L["Wr"]), to_dev(L["b"]), dev=(Wg, Wu, Wd))
+    X = to_dev(L["X"])
+    out = torch.empty_like(X)
+    ws = B.alloc_workspace(sh)
+    ws.view(torch.uint8).fill_(0xAB)          # nothing may rely on what the workspace held
+    B.moe_layer_forward(ctx, sh, layer, X, out, ws)
+    torch.cuda.synchronize()
+    v = B.moe_workspace_views(sh, ws)
+    ref = O.moe_layer(L["X"], L["Wr"], L["b"], L["Wg"], L["Wu"], L["Wd"], k, S)
+    idx = v["topk_idx"].cpu().numpy()
+    assert np.array_equal(idx, ref["topk_idx"])
+    count, offset, perm, inv = O.bucket_by_expert(ref["topk_idx"], E)
+    assert np.array_equal(v["count"].cpu().numpy(), count)
+    assert np.array_equal(v["offset"].cpu().numpy(), offset)
+    assert np.array_equal(v["perm"].cpu().numpy(), perm)
+    assert np.array_equal(v["inv_perm"].cpu().numpy(), inv)
+    assert row_rel_err(O.widen(to_host_bits(out)), ref["out"]) <= TOL["bf16"]
+    ctx.close()
