@@ -133,7 +133,8 @@ struct OneTokenBuckets {
 __device__ __forceinline__ void select_topk(double c0, double c1, int E, int k, bool store, size_t t,
                                             int lane, int32_t* __restrict__ topk_idx,
                                             float* __restrict__ topk_w,
-                                            OneTokenBuckets one = OneTokenBuckets{nullptr, nullptr, nullptr, nullptr}) {
+                                            OneTokenBuckets one = OneTokenBuckets{nullptr, nullptr, nullptr, nullptr},
+                                            int32_t* lds_sel = nullptr) {
   const int e0 = lane, e1 = lane + MOE_WAVE;
   uint64_t key0 = e0 < E ? sortable_key(c0) : 0ull;
   uint64_t key1 = e1 < E ? sortable_key(c1) : 0ull;
@@ -175,6 +176,7 @@ __device__ __forceinline__ void select_topk(double c0, double c1, int E, int k, 
   if (store && lane < k) {
     topk_idx[t * k + lane] = sel_i;
     topk_w[t * k + lane] = ex / sum;
+    if (lds_sel) lds_sel[t * k + lane] = sel_i;
   }
   // A batch of one token: its k assignments are the whole list, so the buckets
   // are known here and the bucketing launch is saved (a tenth of a one-token
@@ -436,9 +438,15 @@ constexpr long kMfmaTiles = 128;   // 16 x 16 logit tiles from which the matrix-
 
 // Selection as a launch of its own (E larger than one logits block): one
 // wavefront per token.
+// With `all` set (the launcher passes it for batches of at most kSelectWaves
+// tokens, i.e. a single workgroup, and k <= 16) the workgroup also buckets: the
+// waves leave their selections in LDS, and the first wave, one lane per
+// assignment (at most 64), counts and ranks them exactly as for a single token
+// (see select_topk) -- the bucketing launch is saved for these batches too.
 __global__ __launch_bounds__(kSelectWaves* MOE_WAVE) void route_select_kernel(
     const double* __restrict__ logits, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
-    int T, int E, int k, OneTokenBuckets one) {
+    int T, int E, int k, OneTokenBuckets all) {
+  __shared__ int32_t s_sel[MOE_WAVE];
   const int lane = threadIdx.x & (MOE_WAVE - 1);
   const int tk = threadIdx.x / MOE_WAVE;
   const int t = min(blockIdx.x * kSelectWaves + tk, T - 1);
@@ -446,7 +454,35 @@ __global__ __launch_bounds__(kSelectWaves* MOE_WAVE) void route_select_kernel(
   const int e0 = lane, e1 = lane + MOE_WAVE;
   const double c0 = e0 < E ? logits[(size_t)t * E + e0] : 0.0;
   const double c1 = e1 < E ? logits[(size_t)t * E + e1] : 0.0;
-  select_topk(c0, c1, E, k, store, (size_t)t, lane, topk_idx, topk_w, store ? one : OneTokenBuckets{});
+  select_topk(c0, c1, E, k, store, (size_t)t, lane, topk_idx, topk_w, OneTokenBuckets{},
+              all.count != nullptr ? s_sel : nullptr);
+  if (all.count == nullptr) return;   // uniform over the launch
+  __syncthreads();
+  if (tk != 0) return;
+  const int A = T * k;                // at most 64
+  const int32_t mine = lane < A ? s_sel[lane] : 0x7fffffff;
+  int n0 = 0, n1 = 0, less0 = 0, less1 = 0, pos = 0;
+  for (int i = 0; i < A; ++i) {
+    const int32_t v = __builtin_amdgcn_readlane(mine, i);
+    n0 += v == e0;
+    n1 += v == e1;
+    less0 += v < e0;
+    less1 += v < e1;
+    pos += v < mine || (v == mine && i < lane);
+  }
+  if (e0 < E) {
+    all.count[e0] = n0;
+    all.offset[e0] = less0;
+  }
+  if (e1 < E) {
+    all.count[e1] = n1;
+    all.offset[e1] = less1;
+  }
+  if (lane == 0) all.offset[E] = A;
+  if (lane < A) {
+    all.perm[pos] = lane;
+    all.inv_perm[lane] = pos;
+  }
 }
 
 // Returns true when the launch also selected (fused form).
@@ -545,7 +581,10 @@ moe_status launch_route_bucket(const moe_shape& s, const void* X, const void* Wr
                                int32_t* topk_idx, float* topk_w, double* logits, int32_t* count,
                                int32_t* offset, int32_t* perm, int32_t* inv_perm, hipStream_t stream,
                                bool* bucketed) {
-  *bucketed = s.T == 1 && s.k <= MOE_WAVE;
+  // the fused router of E <= 8 runs one workgroup per token: a single token only; the selecting
+  // launch of its own has one workgroup up to kSelectWaves tokens
+  const bool fused = s.E <= 8 && s.T <= 1024;   // as launch_logits decides
+  *bucketed = s.k <= 16 && (fused ? s.T == 1 : s.T <= kSelectWaves);
   const OneTokenBuckets one = *bucketed ? OneTokenBuckets{count, offset, perm, inv_perm} : OneTokenBuckets{};
   return route_impl(s, X, Wr, bias, topk_idx, topk_w, logits, stream, one);
 }

@@ -903,13 +903,16 @@ def test_stage_probe_runs_and_leaves_its_inputs_alone(B):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("T", [1, 2, 3, 4, 5])
 @pytest.mark.parametrize("E,k,S", [(8, 2, 0), (8, 8, 0), (60, 4, 2), (128, 8, 0), (128, 16, 8), (1, 1, 0)])
-def test_one_token_buckets_come_from_the_selecting_launch(B, E, k, S):
-    """A batch of one token is bucketed by the launch that selects (no bucketing launch):
-    count, offset, perm and inv_perm must be what the oracle's stable bucketing gives."""
-    cfg = _small(f"one_{E}_{k}_{S}", T=1, E=E, k=k, S=S, H=256, F=128, bias="normal")
+def test_smallest_batches_are_bucketed_by_the_selecting_launch(B, E, k, S, T):
+    """One token (any router), or up to four tokens when selection is a launch of its own (E > 8),
+    are bucketed by the launch that selects -- there is no bucketing launch; five tokens, and two to
+    four with the fused router of E <= 8, take the bucketing launch.  Either way count, offset, perm
+    and inv_perm must be what the oracle's stable bucketing gives."""
+    cfg = _small(f"few_{T}_{E}_{k}_{S}", T=T, E=E, k=k, S=S, H=256, F=128, bias="normal", bias_scale=1.0)
     L = make_layer(cfg)
-    sh = _shape(B, cfg, 1)
+    sh = _shape(B, cfg, T)
     ctx = B.Context(sh)
     Wg, Wu, Wd = _experts_dev(B, L, "row_major")
     layer = B.make_layer_desc(sh, to_dev(L["Wr"]), to_dev(L["b"]), dev=(Wg, Wu, Wd))
@@ -921,6 +924,8 @@ def test_one_token_buckets_come_from_the_selecting_launch(B, E, k, S):
     torch.cuda.synchronize()
     v = B.moe_workspace_views(sh, ws)
     ref = O.moe_layer(L["X"], L["Wr"], L["b"], L["Wg"], L["Wu"], L["Wd"], k, S)
+    if E > 1 and O.routing_margins(ref["logits"], k).min() <= 1e-9:
+        pytest.skip("ill-posed routing for this seed")
     idx = v["topk_idx"].cpu().numpy()
     assert np.array_equal(idx, ref["topk_idx"])
     count, offset, perm, inv = O.bucket_by_expert(ref["topk_idx"], E)
